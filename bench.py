@@ -1,0 +1,300 @@
+#!/usr/bin/env python3
+"""Benchmark of the Moment-KV decode hot path on one MI355X.
+
+A "step" is one pass of the whole hot path -- append, split-K attention with logit emission,
+split merge + head mean + momentum update, and (when the decode pool exceeds its trigger) selection
+and in-place compaction -- for every sequence of every layer of the workload, on synthetic inputs
+that are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = microseconds per decode step per layer (lower is better), with
+tokens/s and the whole-step algorithmic GB/s beside it; `roofline` covers the attention kernel,
+timed with HIP events around every launch in a second pass of the same steps; `cpu_baseline` is the
+CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default cfg3: the HBM-bound Llama-3.1-8B-shaped layer)")
+    ap.add_argument("--also", default="cfg2,cfg4,cfg5", help="comma list of further workloads reported under 'others' ('' = none)")
+    ap.add_argument("--split-keys", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    return ap.parse_args()
+
+
+def to_device(torch, X, x, dtype):
+    if dtype == "bf16":
+        return torch.from_numpy(X.bf16_bits(x).view(np.int16)).view(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).cuda()
+
+
+class Job:
+    """One workload resident on the GPU: pools filled, decode pools at the budget, a bank of step
+    inputs on the device."""
+
+    BANK = 64
+
+    def __init__(self, wl, split_keys=0):
+        import torch
+        import paper_2605_29873_amd.binding as mkv
+        from paper_2605_29873_amd import inputs as X
+        self.torch, self.mkv, self.X, self.wl = torch, mkv, X, wl
+        self.tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        self.lens = [X.prefill_len(wl, s) for s in range(wl.batch)]
+        cfg = mkv.make_config(
+            n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
+            head_dim=wl.head_dim, dtype=mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32,
+            max_prefill=wl.prefill_max, decode_budget=wl.decode_budget, evict_trigger=wl.evict_trigger,
+            decode_capacity=wl.capacity, recent_window=wl.recent_window, alpha=wl.alpha,
+            softmax_scale=0.0, score_mode=0, split_keys=split_keys,
+            stream=torch.cuda.current_stream().cuda_stream)
+        self.arena_bytes = mkv.mkv_required_bytes(cfg)
+        self.ctx = mkv.mkv_create(cfg)
+        self._fill()
+        self._bank()
+        self.t = 0
+
+    def _fill(self):
+        """Prefill pools and budget-full decode pools: N(0,1) values drawn on the device (torch's
+        seeded generator), scores of the magnitude a momentum-accumulated attention share has."""
+        torch, mkv, wl = self.torch, self.mkv, self.wl
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(wl.seed)
+        rng = np.random.default_rng(wl.seed)
+        t_now = 4 * wl.capacity
+        shape_d = (wl.decode_budget, wl.n_kv_heads, wl.head_dim)
+        for layer in range(wl.n_layers):
+            for s in range(wl.batch):
+                m = self.lens[s]
+                if m:
+                    k = torch.randn((m, wl.n_kv_heads, wl.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(self.tdtype)
+                    v = torch.randn((m, wl.n_kv_heads, wl.head_dim), generator=gen, device="cuda", dtype=torch.float32).to(self.tdtype)
+                    mkv.mkv_prefill_append(self.ctx, layer, s, k.data_ptr(), v.data_ptr(), m)
+                kd = torch.randn(shape_d, generator=gen, device="cuda", dtype=torch.float32).to(self.tdtype)
+                vd = torch.randn(shape_d, generator=gen, device="cuda", dtype=torch.float32).to(self.tdtype)
+                pos = np.sort(rng.choice(t_now, wl.decode_budget, replace=False)).astype(np.int32)
+                sc = (rng.random(wl.decode_budget, dtype=np.float32) * 1e-3).astype(np.float32)
+                mkv.mkv_load_decode(self.ctx, layer, s, kd.data_ptr(), vd.data_ptr(), sc, pos, t_now)
+        torch.cuda.synchronize()
+
+    def _bank(self):
+        """BANK consecutive steps of the workload's seeded step inputs, per layer, on the device."""
+        torch, X, wl = self.torch, self.X, self.wl
+        layers = range(wl.n_layers)
+        # layers beyond the first few reuse a rotated copy of the drawn inputs: drawing 32 x BANK x batch
+        # Philox streams on the host would take minutes and adds nothing to a timing run
+        drawn = min(wl.n_layers, 2)
+        per_layer = []
+        for layer in range(drawn):
+            qs, ks, vs = zip(*(X.step_batch(wl, layer, 4 * wl.capacity + t) for t in range(self.BANK)))
+            per_layer.append((to_device(torch, X, np.stack(qs), wl.dtype), to_device(torch, X, np.stack(ks), wl.dtype),
+                              to_device(torch, X, np.stack(vs), wl.dtype)))
+        self.q = [per_layer[l % drawn][0] for l in layers]
+        self.k = [per_layer[l % drawn][1] for l in layers]
+        self.v = [per_layer[l % drawn][2] for l in layers]
+        self.shift = [l // drawn for l in layers]
+        self.out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=self.tdtype, device="cuda")
+        torch.cuda.synchronize()
+
+    def close(self):
+        self.mkv.mkv_destroy(self.ctx)
+
+
+def run_steps(job: Job, n: int):
+    mkv, ctx, wl = job.mkv, job.ctx, job.wl
+    out_ptr = job.out.data_ptr()
+    for _ in range(n):
+        for layer in range(wl.n_layers):
+            i = (job.t + job.shift[layer]) % job.BANK
+            mkv.mkv_decode_step(ctx, layer, job.q[layer][i].data_ptr(), job.k[layer][i].data_ptr(),
+                                job.v[layer][i].data_ptr(), out_ptr)
+        job.t += 1
+
+
+def pool_sizes(job: Job):
+    """Decode pool size per sequence of layer 0 (all layers move in step)."""
+    return [job.mkv.mkv_get_lens(job.ctx, 0, s)[1] for s in range(job.wl.batch)]
+
+
+def algorithmic_bytes(job: Job, n_d_before: list[int]):
+    """Bytes the method must move in one decode step of ONE layer, given each sequence's decode
+    pool size before the step: (whole step, attention kernel).  The rows an eviction moves depend
+    on the scores and are left out of the numerator, which is therefore conservative."""
+    wl = job.wl
+    b = wl.itemsize
+    row = wl.n_kv_heads * wl.head_dim * b * 2            # K and V bytes of one token of one layer
+    attn = 0
+    rest = 0
+    for m, n0 in zip(job.lens, n_d_before):
+        n1 = n0 + 1
+        attn += (m + n1) * row                            # K, V read once
+        attn += wl.n_q_heads * wl.head_dim * b            # q read
+        attn += row                                       # append write
+        rest += wl.n_q_heads * wl.head_dim * b            # out write
+        rest += n1 * 4 * 2                                # I read + write
+    return attn + rest, attn
+
+
+def time_region(job: Job, steps: int):
+    torch = job.torch
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    e0.record()
+    run_steps(job, steps)
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return e0.elapsed_time(e1) * 1e-3, wall
+
+
+def measure(wl, steps, warmup, split_keys=0):
+    job = Job(wl, split_keys)
+    try:
+        run_steps(job, warmup)
+        # sizes the pools will have over the timed steps (deterministic: +1 per step, back to the
+        # budget once above the trigger)
+        n_now = pool_sizes(job)
+        total_bytes = attn_bytes = 0
+        evict_steps = 0
+        sim = list(n_now)
+        for _ in range(steps):
+            tb, ab = algorithmic_bytes(job, sim)
+            total_bytes += tb
+            attn_bytes += ab
+            sim = [n + 1 for n in sim]
+            if any(n > wl.evict_trigger for n in sim):
+                evict_steps += 1
+            sim = [wl.decode_budget if n > wl.evict_trigger else n for n in sim]
+        gpu_s, wall_s = time_region(job, steps)
+        # second pass of the same number of steps with per-kernel events
+        job.mkv.mkv_set_profiling(job.ctx, True)
+        run_steps(job, steps)
+        prof, psteps, pevict = job.mkv.mkv_read_profile(job.ctx)
+        job.mkv.mkv_set_profiling(job.ctx, False)
+        n_launch = steps * wl.n_layers
+        assert psteps == n_launch
+        res = {
+            "workload": wl.name,
+            "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
+            "ms_per_step": gpu_s * 1e3 / steps,
+            "wall_ms_per_step": wall_s * 1e3 / steps,
+            "tokens_per_s": wl.batch * steps / gpu_s,
+            "step_algorithmic_GBps": total_bytes * wl.n_layers / gpu_s / 1e9,
+            "step_frac_of_hbm_peak": total_bytes * wl.n_layers / gpu_s / 1e9 / HBM_PEAK_GBPS,
+            "attn_kernel_us": prof["attn_us"] / n_launch,
+            "finish_kernel_us": prof["finish_us"] / n_launch,
+            "evict_us_per_evicting_launch": (prof["evict_us"] / pevict) if pevict else None,
+            "evicting_launches": int(pevict),
+            "attn_algorithmic_bytes_per_launch": attn_bytes / steps,
+            "attn_GBps": (attn_bytes / steps) / (prof["attn_us"] / n_launch * 1e-6) / 1e9,
+            "arena_GB": job.arena_bytes / 1e9,
+            "pool_tokens_per_layer": int(sum(job.lens) + sum(n_now)),
+        }
+        return res
+    finally:
+        job.close()
+
+
+def cpu_baseline(wl, seconds):
+    """The oracle as it stands, one sequence of the workload from a budget-full pool, timed for
+    about `seconds`; scaled to the whole batch (sequences are independent)."""
+    from oracle import momentkv_oracle as O
+    from paper_2605_29873_amd import inputs as X
+    st = O.MomentKVState(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.decode_budget, wl.alpha,
+                         wl.evict_trigger, wl.recent_window)
+    st.prefill_append(*X.prefill_kv(wl, 0, 0))
+    t_now = 4 * wl.capacity
+    st.load_decode(*X.decode_snapshot(wl, 0, 0, wl.decode_budget, t_now), t_now)
+    inputs = [X.step_inputs(wl, 0, 0, t_now + t) for t in range(8)]
+    n = 0
+    c0, t0 = time.process_time(), time.perf_counter()
+    while time.perf_counter() - t0 < seconds and n < 4096:
+        st.decode_step(*inputs[n % len(inputs)])
+        n += 1
+    wall, cpu = time.perf_counter() - t0, time.process_time() - c0
+    per_seq_step_us = wall / n * 1e6
+    return {"value": per_seq_step_us * wl.batch, "unit": "us per decode step per layer",
+            "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+            "sample": f"sequence 0 (prefill {X.prefill_len(wl, 0)}) of layer 0, {n} steps from a budget-full decode pool, "
+                      f"{per_seq_step_us:.0f} us per sequence-step x batch {wl.batch}; numpy fp64"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    import paper_2605_29873_amd.binding as mkv
+    from paper_2605_29873_amd import inputs as X
+    mkv.load()
+    wls = X.workloads()
+    wl = wls[args.workload]
+    main_res = measure(wl, args.steps, args.warmup, args.split_keys)
+    others = {}
+    for name in [n for n in args.also.split(",") if n and n != args.workload]:
+        w = wls[name]
+        # many-layer jobs: one whole eviction cycle (the pools evict every `chunk` steps)
+        chunk = w.evict_trigger - w.decode_budget + 1
+        steps = args.steps if w.n_layers == 1 else max(chunk, 16)
+        warm = args.warmup if w.n_layers == 1 else 8
+        try:
+            others[name] = measure(w, steps, warm, args.split_keys)
+        except Exception as e:  # a side measurement must not lose the main line
+            others[name] = {"error": repr(e)}
+    line = {
+        "metric": "us_per_decode_step_per_layer (attn+score+evict)",
+        "value": main_res["us_per_step_per_layer"],
+        "unit": "us",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": main_res["ms_per_step"],
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "f32 accumulate over bf16 K/V",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": wl.batch, "layers": wl.n_layers,
+                   "heads": f"{wl.n_q_heads}q/{wl.n_kv_heads}kv x {wl.head_dim}",
+                   "prefill": f"{wl.prefill_min}..{wl.prefill_max}", "decode_budget": wl.decode_budget,
+                   "evict_chunk": wl.evict_trigger - wl.decode_budget + 1,
+                   "recent_window": wl.recent_window, "alpha": wl.alpha},
+        "tokens_per_s": main_res["tokens_per_s"],
+        "hbm_GBps_whole_step": main_res["step_algorithmic_GBps"],
+        "hbm_frac_whole_step": main_res["step_frac_of_hbm_peak"],
+        "roofline": {"bound": "hbm", "kernel": "attn_split_kernel",
+                     "achieved": main_res["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": main_res["attn_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": main_res["attn_algorithmic_bytes_per_launch"],
+                     "avg_launch_us": main_res["attn_kernel_us"],
+                     "timing": "HIP events around every launch, second pass of the same steps"},
+        "detail": main_res,
+        "others": others,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

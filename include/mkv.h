@@ -1,0 +1,171 @@
+/*
+ * mkv.h -- C ABI of the Moment-KV decode-step library for AMD MI355X (gfx950).
+ *
+ * The library owns, per (layer, sequence), the two cache pools of the paper's "Cache
+ * Architecture" paragraph -- a frozen prefill pool and a budgeted decode pool -- and the
+ * importance vector I, and runs Algorithm 1 ("Decoding with Moment-KV") on them with HIP
+ * kernels:  append -> attention over the whole pool (Eq. 2) -> head mean of the decode slice
+ * (Eq. 4) -> momentum update (Eq. 5, Eq. 6) -> capacity check (Eq. 7) -> selection of the
+ * lowest-score tokens (Eq. 8) -> removal and compaction (Eq. 9).
+ *
+ * Conventions
+ *   - every function returns MKV_OK (0) or a negative mkv_status; nothing throws or aborts;
+ *     on error the cache state is unchanged and mkv_last_error() describes the reason;
+ *   - "device pointer" = memory of the GPU the context was created on; "host pointer" = ordinary
+ *     process memory.  Each argument says which it is;
+ *   - the context owns the cache memory (or borrows cfg.arena); the caller owns q/k/v/out;
+ *   - all GPU work is enqueued on cfg.stream and is asynchronous, except the mkv_read_* /
+ *     mkv_write_scores / mkv_load_decode calls, which synchronise that stream;
+ *   - a context is not thread-safe: one caller at a time.
+ *
+ * Tensor element type ("storage dtype"): MKV_F32 = IEEE float, MKV_BF16 = bfloat16 (upper 16 bits
+ * of a float).  Scores are always float.  All tensors are dense, row-major, last index fastest.
+ */
+#ifndef MKV_H
+#define MKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mkv_ctx mkv_ctx;
+
+typedef enum { MKV_F32 = 0, MKV_BF16 = 1 } mkv_dtype;
+
+/* MKV_SCORE_LAYER_MEAN: Eq. 4 as printed -- the mean runs over all H query heads, so there is one
+ * score per decode token per (layer, sequence) and a token leaves all KV heads together. */
+typedef enum { MKV_SCORE_LAYER_MEAN = 0 } mkv_score_mode;
+
+typedef enum {
+  MKV_OK = 0,
+  MKV_ERR_ARG = -1,       /* null pointer, index out of range, inconsistent configuration   */
+  MKV_ERR_STATE = -2,     /* call not valid in the current state                             */
+  MKV_ERR_FROZEN = -3,    /* prefill append after the first decode step of that sequence     */
+  MKV_ERR_CAPACITY = -4,  /* prefill or decode pool would exceed its capacity                */
+  MKV_ERR_NOMEM = -5,     /* device allocation failed or the given arena is too small        */
+  MKV_ERR_HIP = -6        /* a HIP runtime call failed                                       */
+} mkv_status;
+
+#define MKV_NEVER_EVICT INT32_MAX
+
+/* Parameters follow Algorithm 1's "Require" line (decoding budget B_d, momentum factor alpha)
+ * plus the shapes, and two generalisations that default to the paper: evict_trigger and
+ * recent_window. */
+typedef struct {
+  int32_t n_layers;        /* independent layers held by this context (>= 1)                     */
+  int32_t batch;           /* sequences per layer (>= 1)                                         */
+  int32_t n_q_heads;       /* H; multiple of n_kv_heads                                          */
+  int32_t n_kv_heads;      /* Hkv; query head h reads KV head h / (H/Hkv)                        */
+  int32_t head_dim;        /* D: 64 or 128                                                       */
+  int32_t dtype;           /* mkv_dtype of q, k, v, out and of the cache                         */
+  int32_t max_prefill;     /* capacity of the frozen pool per sequence (ragged lengths <= this)  */
+  int32_t decode_budget;   /* B_d (Eq. 3, Eq. 7)                                                 */
+  int32_t evict_trigger;   /* T_e >= B_d: mkv_decode_step evicts back to B_d when the decode pool
+                              exceeds T_e.  T_e == B_d is the paper (Alg. 1 "if |pool_d| > B_d").
+                              MKV_NEVER_EVICT: only mkv_evict evicts                            */
+  int32_t decode_capacity; /* decode slots per sequence; 0 => evict_trigger + 1.  Required (> B_d)
+                              with MKV_NEVER_EVICT.  At most 16384                              */
+  int32_t recent_window;   /* W <= B_d: the W newest decode tokens are never evicted.  0 is the
+                              paper ("regardless of position or recency")                       */
+  float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
+  float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
+  int32_t score_mode;      /* mkv_score_mode                                                     */
+  int32_t split_keys;      /* tuning: keys per attention work-group; 0 => library default        */
+  void*   stream;          /* hipStream_t, borrowed; NULL => the default stream                  */
+  void*   arena;           /* optional device pointer, 256-byte aligned, caller-owned, must outlive
+                              the context; NULL => the library allocates and frees              */
+  size_t  arena_bytes;     /* size of arena; must be >= mkv_required_bytes(cfg)                  */
+} mkv_config;
+
+/* Device bytes a context with this configuration needs (0 if the configuration is invalid). */
+size_t mkv_required_bytes(const mkv_config* cfg);
+
+/* Validates cfg (host pointer), allocates or carves the arena, zeroes the bookkeeping.
+ * *out (host pointer) receives the context.  Errors: MKV_ERR_ARG, MKV_ERR_NOMEM, MKV_ERR_HIP. */
+int mkv_create(const mkv_config* cfg, mkv_ctx** out);
+
+/* Waits for the stream, frees what the library allocated.  NULL is MKV_OK. */
+int mkv_destroy(mkv_ctx* ctx);
+
+/* Appends n_tokens prompt tokens to the prefill pool of (layer, seq) -- "Prefill Phase":
+ * the prompt's K_P, V_P written to the prefill pool.  k, v: device pointers
+ * [n_tokens, n_kv_heads, head_dim] in the storage dtype; copied, the caller keeps them.
+ * Repeatable until that sequence's first decode step; afterwards MKV_ERR_FROZEN (the prefill pool
+ * "is retained in full and never evicted").  MKV_ERR_CAPACITY beyond max_prefill. */
+int mkv_prefill_append(mkv_ctx* ctx, int layer, int seq, const void* k, const void* v, int n_tokens);
+
+/* One pass of Algorithm 1 for every active sequence of one layer.
+ *   q     device pointer [batch, n_q_heads, head_dim]   the step's queries
+ *   k_new device pointer [batch, n_kv_heads, head_dim]  appended to the decode pool with I = 0
+ *   v_new device pointer [batch, n_kv_heads, head_dim]
+ *   out   device pointer [batch, n_q_heads, head_dim]   Att_t of Eq. 2 (rows of inactive
+ *                                                       sequences are left untouched)
+ *   seq_mask host pointer [batch] or NULL; 0 = sequence skipped this step (no append, no update)
+ * Attention runs over prefill + decode pool including the new token; the decode slice of the
+ * softmax, averaged over all query heads, updates I by Eq. 5; then every active sequence whose
+ * decode pool exceeds evict_trigger is evicted back to decode_budget (Eq. 7-9).
+ * MKV_ERR_CAPACITY if an active sequence has no free decode slot (only with MKV_NEVER_EVICT). */
+int mkv_decode_step(mkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
+                    void* out, const uint8_t* seq_mask);
+
+/* Capacity enforcement on demand (Eq. 7-9): every selected sequence whose decode pool exceeds
+ * decode_budget loses its overflow lowest-score tokens outside the recent window -- ties go to
+ * the older token -- and the survivors' K, V, score and position rows are compacted in order of
+ * generation.  seq = -1: all sequences of the layer.  MKV_OK and no effect when within budget. */
+int mkv_evict(mkv_ctx* ctx, int layer, int seq);
+
+/* Reads the importance vector (Eq. 5) and the original decode positions of (layer, seq) into host
+ * buffers of `capacity` entries; *n_out = decode pool size.  Either buffer may be NULL.
+ * MKV_ERR_CAPACITY if capacity is too small. */
+int mkv_read_scores(mkv_ctx* ctx, int layer, int seq, float* scores, int32_t* positions,
+                    int capacity, int* n_out);
+
+/* ---- parity / snapshot helpers (not on the hot path) ---------------------------------------- */
+
+/* Overwrites the first n scores of (layer, seq) from a host buffer; n must equal the pool size. */
+int mkv_write_scores(mkv_ctx* ctx, int layer, int seq, const float* scores, int n);
+
+/* Restores a decode pool: k, v device pointers [n, n_kv_heads, head_dim]; scores, positions host
+ * pointers [n] (positions strictly increasing, all < next_step).  Replaces the decode pool of
+ * (layer, seq), sets its step counter to next_step and freezes its prefill pool. */
+int mkv_load_decode(mkv_ctx* ctx, int layer, int seq, const void* k, const void* v,
+                    const float* scores, const int32_t* positions, int n, int64_t next_step);
+
+/* Copies one KV head of a pool to host buffers [n, head_dim] (storage dtype).
+ * pool: 0 = decode pool, 1 = prefill pool.  Either buffer may be NULL. */
+int mkv_read_kv(mkv_ctx* ctx, int layer, int seq, int pool, int kv_head, void* k, void* v,
+                int capacity, int* n_out);
+
+/* After mkv_decode_step(layer): the head-mean decode-slice attention abar (Eq. 4) the step added
+ * to the scores, for the pool as it was before that step's eviction (host float[capacity]), and the
+ * natural-log softmax normaliser per query head (host float[n_q_heads]).  Either may be NULL.
+ * MKV_ERR_STATE if `layer` was not the layer stepped last. */
+int mkv_read_probs(mkv_ctx* ctx, int layer, int seq, float* abar, float* lse_per_head,
+                   int capacity, int* n_out);
+
+/* Host-side bookkeeping of (layer, seq): prefill length, decode pool size, decode steps taken. */
+int mkv_get_lens(mkv_ctx* ctx, int layer, int seq, int* n_prefill, int* n_decode, int64_t* step);
+
+/* ---- measurement helper (off by default) ---------------------------------------------------- */
+
+/* enable != 0: every following mkv_decode_step brackets its attention kernel, its finishing
+ * kernel and its eviction kernels with HIP events on the context's stream (this slows the step a
+ * little: use a separate pass for whole-step timing).  enable == 0 stops recording.  Either way
+ * the accumulated figures are reset. */
+int mkv_set_profiling(mkv_ctx* ctx, int enable);
+
+/* Waits for the stream and returns the sums since mkv_set_profiling: microseconds spent in the
+ * attention, finishing and eviction kernels (host pointers to 3 doubles) and the number of steps
+ * and of steps that evicted (host pointers to 2 int64).  Any pointer may be NULL. */
+int mkv_read_profile(mkv_ctx* ctx, double* kernel_us, int64_t* counts);
+
+/* Text of the last error on this context (or of the last failed mkv_create when ctx is NULL). */
+const char* mkv_last_error(const mkv_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MKV_H */

@@ -1,0 +1,550 @@
+// Host side of the C ABI declared in include/mkv.h: configuration checks, arena layout,
+// host mirror of the per-sequence lengths, and the launch sequence of one decode step
+// (Algorithm 1).  No arithmetic of the method happens here.
+#include "../../include/mkv.h"
+#include "mkv_internal.h"
+
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace mkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int kDefaultSplitKeys = 512;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+  // per-layer regions (byte offsets inside a layer block) and the layer stride
+  size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
+  // scratch regions (absolute offsets), shared by all layers
+  size_t part_o, part_ml, logits, abar, lse, src_map, evict_info, total;
+  int cap, CH, S_max;
+};
+
+thread_local std::string g_create_error;
+
+std::string fmt(const char* f, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, f);
+  vsnprintf(buf, sizeof buf, f, ap);
+  va_end(ap);
+  return buf;
+}
+
+// Returns an empty string when cfg is usable, else the reason.
+std::string check_config(const mkv_config* c) {
+  if (!c) return "cfg is NULL";
+  if (c->n_layers < 1 || c->batch < 1) return "n_layers and batch must be >= 1";
+  if (c->batch > kMaxBatch) return fmt("batch %d above the supported %d", c->batch, kMaxBatch);
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads != 0)
+    return "n_q_heads must be a positive multiple of n_kv_heads";
+  if (c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 64 or 128";
+  if (c->dtype != MKV_F32 && c->dtype != MKV_BF16) return "dtype must be MKV_F32 or MKV_BF16";
+  if (c->max_prefill < 0) return "max_prefill must be >= 0";
+  if (c->decode_budget < 1) return "decode_budget must be >= 1";
+  if (c->evict_trigger < c->decode_budget) return "evict_trigger must be >= decode_budget";
+  if (c->recent_window < 0 || c->recent_window > c->decode_budget)
+    return "recent_window must lie in [0, decode_budget]";
+  if (!(c->alpha >= 0.0f && c->alpha <= 1.0f)) return "alpha must lie in [0, 1]";
+  if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return "softmax_scale must be finite and >= 0";
+  if (c->score_mode != MKV_SCORE_LAYER_MEAN) return "unknown score_mode";
+  if (c->split_keys < 0 || (c->split_keys % 64) != 0) return "split_keys must be a non-negative multiple of 64";
+  int64_t cap = c->decode_capacity;
+  if (cap == 0) {
+    if (c->evict_trigger == MKV_NEVER_EVICT) return "decode_capacity is required with MKV_NEVER_EVICT";
+    cap = (int64_t)c->evict_trigger + 1;
+  }
+  if (cap <= c->decode_budget) return "decode_capacity must exceed decode_budget";
+  if (c->evict_trigger != MKV_NEVER_EVICT && cap < (int64_t)c->evict_trigger + 1)
+    return "decode_capacity must be at least evict_trigger + 1";
+  if (cap > kMaxDecodeCapacity) return fmt("decode capacity %lld above the supported %d", (long long)cap, kMaxDecodeCapacity);
+  if (c->arena && ((uintptr_t)c->arena % kAlign) != 0) return "arena must be 256-byte aligned";
+  return "";
+}
+
+Layout make_layout(const mkv_config* c) {
+  Layout L;
+  memset(&L, 0, sizeof L);
+  L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + 1;
+  L.CH = c->split_keys ? c->split_keys : kDefaultSplitKeys;
+  L.S_max = (c->max_prefill + L.CH - 1) / L.CH + (L.cap + L.CH - 1) / L.CH;
+  const size_t es = c->dtype == MKV_BF16 ? 2 : 4;
+  const size_t B = c->batch, Hkv = c->n_kv_heads, H = c->n_q_heads, D = c->head_dim;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  L.Kp = take(B * Hkv * (size_t)c->max_prefill * D * es);
+  L.Vp = take(B * Hkv * (size_t)c->max_prefill * D * es);
+  L.Kd = take(B * Hkv * (size_t)L.cap * D * es);
+  L.Vd = take(B * Hkv * (size_t)L.cap * D * es);
+  L.score = take(B * L.cap * 4);
+  L.pos = take(B * L.cap * 4);
+  L.mlen = take(B * 4);
+  L.nd = take(B * 4);
+  L.nd_eff = take(B * 4);
+  L.tpos = take(B * 4);
+  L.layer_bytes = o;
+  o = L.layer_bytes * (size_t)c->n_layers;
+  L.part_o = take(B * H * L.S_max * D * 4);
+  L.part_ml = take(B * H * L.S_max * 2 * 4);
+  L.logits = take(B * H * L.cap * 4);
+  L.abar = take(B * L.cap * 4);
+  L.lse = take(B * H * 4);
+  L.src_map = take(B * L.cap * 4);
+  L.evict_info = take(B * 2 * 4);
+  L.total = o;
+  return L;
+}
+
+__global__ void set_int_kernel(int32_t* p, int32_t v) { *p = v; }
+
+}  // namespace
+
+// Event-bracketed kernel timing, off unless mkv_set_profiling asked for it.
+struct Profiler {
+  static constexpr int kSlots = 512;       // steps recorded before the sums are folded
+  bool on = false;
+  std::vector<hipEvent_t> ev;              // 4 events per slot
+  std::vector<uint8_t> evicted;
+  int used = 0;
+  double us[3] = {0, 0, 0};
+  int64_t steps = 0, evict_steps = 0;
+};
+
+struct mkv_ctx {
+  mkv_config cfg;
+  Layout lay;
+  Shape shape;
+  hipStream_t stream;
+  char* arena;
+  bool own_arena;
+  std::vector<int32_t> h_mlen, h_nd, h_last_n;  // [L*B]; h_last_n [B]: pool size seen by the last step
+  std::vector<int64_t> h_step;
+  std::vector<uint8_t> frozen;
+  int last_layer;
+  std::string err;
+  Profiler prof;
+};
+
+namespace {
+
+int fail(mkv_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg; else g_create_error = msg;
+  return code;
+}
+int fail_hip(mkv_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, MKV_ERR_HIP, fmt("%s: %s", what, hipGetErrorString(e)));
+}
+
+LayerView layer_view(const mkv_ctx* c, int layer) {
+  char* base = c->arena + c->lay.layer_bytes * (size_t)layer;
+  LayerView v;
+  v.Kp = base + c->lay.Kp; v.Vp = base + c->lay.Vp;
+  v.Kd = base + c->lay.Kd; v.Vd = base + c->lay.Vd;
+  v.score = (float*)(base + c->lay.score);
+  v.pos = (int32_t*)(base + c->lay.pos);
+  v.mlen = (int32_t*)(base + c->lay.mlen);
+  v.nd = (int32_t*)(base + c->lay.nd);
+  v.nd_eff = (int32_t*)(base + c->lay.nd_eff);
+  v.tpos = (int32_t*)(base + c->lay.tpos);
+  return v;
+}
+
+Scratch scratch_view(const mkv_ctx* c) {
+  Scratch s;
+  s.part_o = (float*)(c->arena + c->lay.part_o);
+  s.part_ml = (float*)(c->arena + c->lay.part_ml);
+  s.logits = (float*)(c->arena + c->lay.logits);
+  s.abar = (float*)(c->arena + c->lay.abar);
+  s.lse = (float*)(c->arena + c->lay.lse);
+  s.src_map = (int32_t*)(c->arena + c->lay.src_map);
+  s.evict_info = (int32_t*)(c->arena + c->lay.evict_info);
+  return s;
+}
+
+// Folds the recorded slots into the sums (waits for the last recorded event).
+hipError_t prof_fold(mkv_ctx* c) {
+  Profiler& p = c->prof;
+  if (p.used == 0) return hipSuccess;
+  hipError_t e = hipEventSynchronize(p.ev[(size_t)(p.used - 1) * 4 + 3]);
+  for (int i = 0; i < p.used && e == hipSuccess; ++i) {
+    hipEvent_t* q = &p.ev[(size_t)i * 4];
+    float ms[3] = {0, 0, 0};
+    e = hipEventElapsedTime(&ms[0], q[0], q[1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms[1], q[1], q[2]);
+    if (e == hipSuccess && p.evicted[i]) e = hipEventElapsedTime(&ms[2], q[2], q[3]);
+    for (int k = 0; k < 3; ++k) p.us[k] += 1000.0 * ms[k];
+    p.steps += 1;
+    p.evict_steps += p.evicted[i];
+  }
+  p.used = 0;
+  return e;
+}
+
+bool bad_index(const mkv_ctx* c, int layer, int seq) {
+  return layer < 0 || layer >= c->cfg.n_layers || seq < 0 || seq >= c->cfg.batch;
+}
+
+int set_device_int(mkv_ctx* c, int32_t* p, int32_t v) {
+  hipLaunchKernelGGL(set_int_kernel, dim3(1), dim3(1), 0, c->stream, p, v);
+  hipError_t e = hipGetLastError();
+  return e == hipSuccess ? MKV_OK : fail_hip(c, e, "set_int launch");
+}
+
+// Evicts the sequences of `mask` whose mirror length exceeds `threshold`; returns MKV_OK when no
+// sequence qualifies.
+int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* fired = nullptr) {
+  const int B = c->cfg.batch;
+  bool any = false;
+  for (int b = 0; b < B; ++b)
+    if (mask.active(b) && c->h_nd[(size_t)layer * B + b] > threshold &&
+        c->h_nd[(size_t)layer * B + b] > c->cfg.decode_budget) any = true;
+  if (fired) *fired = any;
+  if (!any) return MKV_OK;
+  hipError_t e = launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "evict launch");
+  for (int b = 0; b < B; ++b) {
+    int32_t& n = c->h_nd[(size_t)layer * B + b];
+    if (mask.active(b) && n > threshold && n > c->cfg.decode_budget) n = c->cfg.decode_budget;
+  }
+  return MKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mkv_required_bytes(const mkv_config* cfg) {
+  if (!check_config(cfg).empty()) return 0;
+  return make_layout(cfg).total;
+}
+
+int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
+  if (!out) return fail(nullptr, MKV_ERR_ARG, "out is NULL");
+  *out = nullptr;
+  std::string why = check_config(cfg);
+  if (!why.empty()) return fail(nullptr, MKV_ERR_ARG, why);
+  mkv_ctx* c = new (std::nothrow) mkv_ctx();
+  if (!c) return fail(nullptr, MKV_ERR_NOMEM, "host allocation failed");
+  c->cfg = *cfg;
+  c->lay = make_layout(cfg);
+  c->stream = (hipStream_t)cfg->stream;
+  c->last_layer = -1;
+  if (cfg->arena) {
+    if (cfg->arena_bytes < c->lay.total) {
+      std::string m = fmt("arena of %zu bytes given, %zu needed", cfg->arena_bytes, c->lay.total);
+      delete c;
+      return fail(nullptr, MKV_ERR_NOMEM, m);
+    }
+    c->arena = (char*)cfg->arena;
+    c->own_arena = false;
+  } else {
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, c->lay.total);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      std::string m = fmt("hipMalloc of %zu bytes: %s", c->lay.total, hipGetErrorString(e));
+      delete c;
+      return fail(nullptr, MKV_ERR_NOMEM, m);
+    }
+    c->arena = (char*)p;
+    c->own_arena = true;
+  }
+  Shape& s = c->shape;
+  s.B = cfg->batch; s.H = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.G = s.H / s.Hkv;
+  s.D = cfg->head_dim; s.bf16 = cfg->dtype == MKV_BF16;
+  s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.CH = c->lay.CH; s.S_max = c->lay.S_max;
+  s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
+  const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
+  s.scale_log2 = (float)(scale * 1.4426950408889634074);
+  const size_t LB = (size_t)cfg->n_layers * cfg->batch;
+  c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0);
+  c->h_last_n.assign(cfg->batch, 0);
+  hipError_t e = configure_kernels();
+  // bookkeeping starts at zero: scores, positions, all lengths, the scratch
+  for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
+    char* base = c->arena + c->lay.layer_bytes * (size_t)l;
+    e = hipMemsetAsync(base + c->lay.score, 0, c->lay.layer_bytes - c->lay.score, c->stream);
+  }
+  if (e == hipSuccess)
+    e = hipMemsetAsync(c->arena + c->lay.part_o, 0, c->lay.total - c->lay.part_o, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) {
+    std::string m = fmt("context initialisation: %s", hipGetErrorString(e));
+    if (c->own_arena) (void)hipFree(c->arena);
+    delete c;
+    return fail(nullptr, MKV_ERR_HIP, m);
+  }
+  *out = c;
+  return MKV_OK;
+}
+
+int mkv_destroy(mkv_ctx* c) {
+  if (!c) return MKV_OK;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  for (hipEvent_t ev : c->prof.ev) (void)hipEventDestroy(ev);
+  if (c->own_arena) {
+    hipError_t e2 = hipFree(c->arena);
+    if (e == hipSuccess) e = e2;
+  }
+  delete c;
+  return e == hipSuccess ? MKV_OK : MKV_ERR_HIP;
+}
+
+int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void* v, int n_tokens) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  if (n_tokens < 0 || (n_tokens > 0 && (!k || !v))) return fail(c, MKV_ERR_ARG, "k/v NULL or n_tokens < 0");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  if (c->frozen[i]) return fail(c, MKV_ERR_FROZEN, "prefill pool is frozen after the first decode step");
+  if ((int64_t)c->h_mlen[i] + n_tokens > c->cfg.max_prefill)
+    return fail(c, MKV_ERR_CAPACITY, fmt("prefill %d + %d exceeds max_prefill %d", c->h_mlen[i], n_tokens, c->cfg.max_prefill));
+  if (n_tokens == 0) return MKV_OK;
+  LayerView lv = layer_view(c, layer);
+  hipError_t e = launch_ingest(c->shape, lv.Kp, lv.Vp, c->cfg.max_prefill, seq, c->h_mlen[i], k, v, n_tokens, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "ingest launch");
+  int rc = set_device_int(c, lv.mlen + seq, c->h_mlen[i] + n_tokens);
+  if (rc != MKV_OK) return rc;
+  c->h_mlen[i] += n_tokens;
+  return MKV_OK;
+}
+
+int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, const void* v_new,
+                    void* out, const uint8_t* seq_mask) {
+  if (!c) return MKV_ERR_ARG;
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
+  if (!q || !k_new || !v_new || !out) return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must not be NULL");
+  const int B = c->cfg.batch;
+  const int CH = c->lay.CH;
+  SeqMask mask;
+  memset(&mask, 0, sizeof mask);
+  int n_active = 0, grid_splits = 0, max_n1 = 0;
+  for (int b = 0; b < B; ++b) {
+    if (seq_mask && !seq_mask[b]) continue;
+    const size_t i = (size_t)layer * B + b;
+    if (c->h_nd[i] >= c->lay.cap)
+      return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: decode pool is full (%d slots)", b, c->lay.cap));
+    mask.w[b >> 6] |= 1ull << (b & 63);
+    ++n_active;
+    const int n1 = c->h_nd[i] + 1;
+    const int ns = (c->h_mlen[i] + CH - 1) / CH + (n1 + CH - 1) / CH;
+    if (ns > grid_splits) grid_splits = ns;
+    if (n1 > max_n1) max_n1 = n1;
+  }
+  if (n_active == 0) return MKV_OK;
+  LayerView lv = layer_view(c, layer);
+  Scratch sc = scratch_view(c);
+  hipEvent_t* pe = nullptr;
+  if (c->prof.on) {
+    if (c->prof.used == Profiler::kSlots) {
+      hipError_t pe_err = prof_fold(c);
+      if (pe_err != hipSuccess) return fail_hip(c, pe_err, "profile events");
+    }
+    pe = &c->prof.ev[(size_t)c->prof.used * 4];
+    c->prof.evicted[c->prof.used] = 0;
+    (void)hipEventRecord(pe[0], c->stream);
+  }
+  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, grid_splits, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "attention launch");
+  if (pe) (void)hipEventRecord(pe[1], c->stream);
+  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "finish launch");
+  if (pe) (void)hipEventRecord(pe[2], c->stream);
+  for (int b = 0; b < B; ++b) {
+    if (!mask.active(b)) continue;
+    const size_t i = (size_t)layer * B + b;
+    c->h_nd[i] += 1;
+    c->h_step[i] += 1;
+    c->frozen[i] = 1;
+    c->h_last_n[b] = c->h_nd[i];
+  }
+  c->last_layer = layer;
+  int rc = MKV_OK;
+  if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
+    bool fired = false;
+    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired);
+    if (pe && fired) {
+      (void)hipEventRecord(pe[3], c->stream);
+      c->prof.evicted[c->prof.used] = 1;
+    }
+  }
+  if (pe) {
+    if (!c->prof.evicted[c->prof.used]) (void)hipEventRecord(pe[3], c->stream);
+    c->prof.used += 1;
+  }
+  return rc;
+}
+
+int mkv_evict(mkv_ctx* c, int layer, int seq) {
+  if (!c) return MKV_ERR_ARG;
+  if (layer < 0 || layer >= c->cfg.n_layers || seq < -1 || seq >= c->cfg.batch)
+    return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  SeqMask mask;
+  memset(&mask, 0, sizeof mask);
+  for (int b = 0; b < c->cfg.batch; ++b)
+    if (seq < 0 || b == seq) mask.w[b >> 6] |= 1ull << (b & 63);
+  return run_evict(c, layer, mask, c->cfg.decode_budget);
+}
+
+int mkv_read_scores(mkv_ctx* c, int layer, int seq, float* scores, int32_t* positions, int capacity,
+                    int* n_out) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  LayerView lv = layer_view(c, layer);
+  int32_t n_dev = -1;
+  hipError_t e = hipMemcpyAsync(&n_dev, lv.nd + seq, 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "read pool size");
+  if (n_dev != c->h_nd[i])
+    return fail(c, MKV_ERR_STATE, fmt("device pool size %d differs from the host mirror %d", n_dev, c->h_nd[i]));
+  if (n_out) *n_out = n_dev;
+  if ((scores || positions) && capacity < n_dev) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
+  if (scores && n_dev) e = hipMemcpyAsync(scores, lv.score + (size_t)seq * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && positions && n_dev)
+    e = hipMemcpyAsync(positions, lv.pos + (size_t)seq * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "read scores");
+  return MKV_OK;
+}
+
+int mkv_write_scores(mkv_ctx* c, int layer, int seq, const float* scores, int n) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq) || !scores) return fail(c, MKV_ERR_ARG, "bad index or NULL scores");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  if (n != c->h_nd[i]) return fail(c, MKV_ERR_ARG, fmt("n = %d but the pool holds %d", n, c->h_nd[i]));
+  if (n == 0) return MKV_OK;
+  LayerView lv = layer_view(c, layer);
+  hipError_t e = hipMemcpyAsync(lv.score + (size_t)seq * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "write scores");
+  return MKV_OK;
+}
+
+int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v, const float* scores,
+                    const int32_t* positions, int n, int64_t next_step) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  if (n < 0 || (n > 0 && (!k || !v || !scores || !positions))) return fail(c, MKV_ERR_ARG, "NULL input or n < 0");
+  if (n > c->lay.cap) return fail(c, MKV_ERR_CAPACITY, fmt("n = %d above the decode capacity %d", n, c->lay.cap));
+  if (next_step < 0 || next_step > INT32_MAX) return fail(c, MKV_ERR_ARG, "next_step out of range");
+  for (int j = 0; j < n; ++j) {
+    if (positions[j] < 0 || positions[j] >= next_step || (j && positions[j] <= positions[j - 1]))
+      return fail(c, MKV_ERR_ARG, "positions must be strictly increasing and below next_step");
+  }
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  LayerView lv = layer_view(c, layer);
+  hipError_t e = launch_ingest(c->shape, lv.Kd, lv.Vd, c->lay.cap, seq, 0, k, v, n, c->stream);
+  if (e == hipSuccess && n)
+    e = hipMemcpyAsync(lv.score + (size_t)seq * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  if (e == hipSuccess && n)
+    e = hipMemcpyAsync(lv.pos + (size_t)seq * c->lay.cap, positions, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "load decode pool");
+  int rc = set_device_int(c, lv.nd + seq, n);
+  if (rc == MKV_OK) rc = set_device_int(c, lv.tpos + seq, (int32_t)next_step);
+  if (rc != MKV_OK) return rc;
+  e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "load decode pool");
+  c->h_nd[i] = n;
+  c->h_step[i] = next_step;
+  c->frozen[i] = 1;
+  return MKV_OK;
+}
+
+int mkv_read_kv(mkv_ctx* c, int layer, int seq, int pool, int kv_head, void* k, void* v, int capacity,
+                int* n_out) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq) || kv_head < 0 || kv_head >= c->cfg.n_kv_heads || (pool != 0 && pool != 1))
+    return fail(c, MKV_ERR_ARG, "bad layer, seq, pool or kv_head");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  const int n = pool ? c->h_mlen[i] : c->h_nd[i];
+  if (n_out) *n_out = n;
+  if ((k || v) && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
+  LayerView lv = layer_view(c, layer);
+  const size_t rowb = (size_t)c->cfg.head_dim * (c->cfg.dtype == MKV_BF16 ? 2 : 4);
+  const size_t rows = pool ? (size_t)c->cfg.max_prefill : (size_t)c->lay.cap;
+  const size_t off = ((size_t)seq * c->cfg.n_kv_heads + kv_head) * rows * rowb;
+  hipError_t e = hipSuccess;
+  if (k && n) e = hipMemcpyAsync(k, (char*)(pool ? lv.Kp : lv.Kd) + off, n * rowb, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && v && n)
+    e = hipMemcpyAsync(v, (char*)(pool ? lv.Vp : lv.Vd) + off, n * rowb, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "read kv");
+  return MKV_OK;
+}
+
+int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_head, int capacity,
+                   int* n_out) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  if (layer != c->last_layer) return fail(c, MKV_ERR_STATE, "layer was not the layer stepped last");
+  const int n = c->h_last_n[seq];
+  if (n_out) *n_out = n;
+  if (abar && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
+  Scratch sc = scratch_view(c);
+  hipError_t e = hipSuccess;
+  if (abar && n) e = hipMemcpyAsync(abar, sc.abar + (size_t)seq * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && lse_per_head)
+    e = hipMemcpyAsync(lse_per_head, sc.lse + (size_t)seq * c->cfg.n_q_heads, (size_t)c->cfg.n_q_heads * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "read probs");
+  if (lse_per_head)
+    for (int h = 0; h < c->cfg.n_q_heads; ++h) lse_per_head[h] *= 0.69314718055994530942f;  // base 2 -> e
+  return MKV_OK;
+}
+
+int mkv_get_lens(mkv_ctx* c, int layer, int seq, int* n_prefill, int* n_decode, int64_t* step) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  if (n_prefill) *n_prefill = c->h_mlen[i];
+  if (n_decode) *n_decode = c->h_nd[i];
+  if (step) *step = c->h_step[i];
+  return MKV_OK;
+}
+
+int mkv_set_profiling(mkv_ctx* c, int enable) {
+  if (!c) return MKV_ERR_ARG;
+  Profiler& p = c->prof;
+  hipError_t e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "stream synchronize");
+  if (enable && p.ev.empty()) {
+    p.ev.resize((size_t)Profiler::kSlots * 4);
+    p.evicted.assign(Profiler::kSlots, 0);
+    for (size_t i = 0; i < p.ev.size(); ++i) {
+      e = hipEventCreate(&p.ev[i]);
+      if (e != hipSuccess) {
+        for (size_t k = 0; k < i; ++k) (void)hipEventDestroy(p.ev[k]);
+        p.ev.clear();
+        return fail_hip(c, e, "hipEventCreate");
+      }
+    }
+  }
+  p.on = enable != 0;
+  p.used = 0;
+  p.us[0] = p.us[1] = p.us[2] = 0.0;
+  p.steps = p.evict_steps = 0;
+  return MKV_OK;
+}
+
+int mkv_read_profile(mkv_ctx* c, double* kernel_us, int64_t* counts) {
+  if (!c) return MKV_ERR_ARG;
+  hipError_t e = prof_fold(c);
+  if (e != hipSuccess) return fail_hip(c, e, "profile events");
+  if (kernel_us) for (int k = 0; k < 3; ++k) kernel_us[k] = c->prof.us[k];
+  if (counts) { counts[0] = c->prof.steps; counts[1] = c->prof.evict_steps; }
+  return MKV_OK;
+}
+
+const char* mkv_last_error(const mkv_ctx* c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+}  // extern "C"

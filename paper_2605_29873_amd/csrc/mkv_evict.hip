@@ -1,0 +1,255 @@
+// Capacity enforcement: selection of the lowest-score decode tokens (Eq. 8), removal and stable
+// in-place compaction of K, V, scores and positions (Eq. 9), fired by the capacity check (Eq. 7).
+// Also the token-major -> head-major ingest copy used by the prefill pool.
+#include "mkv_internal.h"
+
+namespace mkv {
+namespace {
+
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Order-preserving map float -> uint32 (total order of the reals; -0 is folded onto +0 so that the
+// two zeros tie, as they do under float comparison).
+__device__ __forceinline__ uint32_t ordered_key(uint32_t bits) {
+  if (bits == 0x80000000u) bits = 0u;
+  return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+}
+
+__device__ __forceinline__ int wave_incl_scan(int x, int lane) {
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int y = __shfl_up(x, off);
+    if (lane >= off) x += y;
+  }
+  return x;
+}
+
+// Exclusive prefix sum of one int per thread over the whole block; *total gets the block sum.
+__device__ __forceinline__ int block_excl_scan(int x, int* wave_sums, int* total) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int incl = wave_incl_scan(x, lane);
+  __syncthreads();  // wave_sums may still be read from a previous scan
+  if (lane == 63) wave_sums[wave] = incl;
+  __syncthreads();
+  int base = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < kSelWaves; ++w) {
+    const int v = wave_sums[w];
+    if (w < wave) base += v;
+    tot += v;
+  }
+  *total = tot;
+  return base + incl - x;
+}
+
+struct EvictArgs {
+  Shape s;
+  LayerView lv;
+  Scratch sc;
+  SeqMask mask;
+  int threshold;
+};
+
+// One work-group per sequence.  The pool's scores and positions sit in LDS; a 4-pass, 8-bit
+// most-significant-first radix select finds the value of the overflow-th smallest candidate score;
+// candidates below it leave, and of those equal to it the oldest (lowest slot = smallest position,
+// because compaction is stable) leave until the count is met.  A prefix sum over the keep flags
+// gives every survivor its new slot; scores and positions are rewritten from LDS, and the
+// new-slot -> old-slot map is left for the row mover.
+__global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictArgs a) {
+  const Shape& s = a.s;
+  const int b = blockIdx.x;
+  if (!a.mask.active(b)) return;
+  const int tid = threadIdx.x;
+  const int n = a.lv.nd[b];
+  int* info = a.sc.evict_info + 2 * b;
+  if (n <= a.threshold || n <= s.budget) {  // Eq. 7: overflow = 0, nothing to do
+    if (tid == 0) { info[0] = n; info[1] = n; }
+    return;
+  }
+  const int k_evict = n - s.budget;   // Eq. 7
+  const int n_cand = n - s.window;    // the newest `window` slots are not candidates
+
+  extern __shared__ uint32_t smem[];
+  uint32_t* raw = smem;               // [cap] score bits
+  int32_t* posl = (int32_t*)(smem + s.cap);  // [cap]
+  __shared__ uint32_t hist[256];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_krem, sh_first;
+  __shared__ int wave_sums[kSelWaves];
+
+  float* score = a.lv.score + (size_t)b * s.cap;
+  int32_t* pos = a.lv.pos + (size_t)b * s.cap;
+  for (int j = tid; j < n; j += kSelThreads) {
+    raw[j] = __builtin_bit_cast(uint32_t, score[j]);
+    posl[j] = pos[j];
+  }
+  if (tid == 0) { sh_prefix = 0u; sh_krem = k_evict; sh_first = n; }
+  __syncthreads();
+
+  // radix select: after the pass for byte `p`, sh_prefix holds the top bytes of the threshold
+  // and sh_krem how many candidates to take among those that match the prefix
+  for (int p = 3; p >= 0; --p) {
+    const int shift = p * 8;
+    const uint32_t himask = (p == 3) ? 0u : (0xffffffffu << (shift + 8));
+    if (tid < 256) hist[tid] = 0u;
+    __syncthreads();
+    const uint32_t prefix = sh_prefix;
+    const int krem = sh_krem;
+    for (int j = tid; j < n_cand; j += kSelThreads) {
+      const uint32_t key = ordered_key(raw[j]);
+      if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+    }
+    __syncthreads();
+    if (tid < 64) {  // wave 0: 4 bins per lane, find the bin that holds the krem-th element
+      const int c0 = hist[4 * tid], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
+      const int sum = c0 + c1 + c2 + c3;
+      const int excl = wave_incl_scan(sum, tid) - sum;
+      if (excl < krem && krem <= excl + sum) {
+        int bin = 4 * tid, below = excl;
+        if (below + c0 < krem) { below += c0; ++bin;
+          if (below + c1 < krem) { below += c1; ++bin;
+            if (below + c2 < krem) { below += c2; ++bin; } } }
+        sh_prefix = prefix | ((uint32_t)bin << shift);
+        sh_krem = krem - below;
+      }
+    }
+    __syncthreads();
+  }
+  const uint32_t thr = sh_prefix;   // ordered key of the overflow-th smallest candidate
+  const int take_eq = sh_krem;      // how many candidates equal to it leave (oldest first)
+
+  // contiguous slots per thread so that prefix sums follow slot order
+  const int items = (n + kSelThreads - 1) / kSelThreads;
+  const int jb = tid * items;
+  const int je = min(n, jb + items);
+  int eq_cnt = 0;
+  for (int j = jb; j < je; ++j) eq_cnt += (j < n_cand && ordered_key(raw[j]) == thr);
+  int total;
+  int eq_rank = block_excl_scan(eq_cnt, wave_sums, &total);
+  int keep_cnt = 0;
+  uint64_t evict_bits = 0;  // items <= 16 by the capacity limit
+  for (int j = jb; j < je; ++j) {
+    bool ev = false;
+    if (j < n_cand) {
+      const uint32_t key = ordered_key(raw[j]);
+      if (key < thr) ev = true;
+      else if (key == thr) { ev = eq_rank < take_eq; ++eq_rank; }
+    }
+    if (ev) evict_bits |= 1ull << (j - jb);
+    else ++keep_cnt;
+  }
+  int dst = block_excl_scan(keep_cnt, wave_sums, &total);
+  int first = n;
+  int32_t* map = a.sc.src_map + (size_t)b * s.cap;
+  for (int j = jb; j < je; ++j) {
+    if ((evict_bits >> (j - jb)) & 1ull) { first = min(first, j); continue; }
+    map[dst] = j;
+    score[dst] = __builtin_bit_cast(float, raw[j]);
+    pos[dst] = posl[j];
+    ++dst;
+  }
+  if (first < n) atomicMin(&sh_first, first);
+  __syncthreads();
+  if (tid == 0) {
+    info[0] = sh_first;   // slots below the first hole stay where they are
+    info[1] = total;      // = budget
+    a.lv.nd[b] = total;
+  }
+}
+
+constexpr int kMoveThreads = 1024;
+constexpr int kMoveUnroll = 4;
+constexpr int kSliceBytes = 64;
+
+// Stable in-place row compaction.  grid (row slices, Hkv * 2, B): a work-group owns a 64-byte
+// column strip of one head's K or V pool and walks the destination slots upwards.  Because a
+// survivor only ever moves to a lower slot, reading a round's sources before a barrier and writing
+// after it can never overwrite a row that is still to be read.
+__global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArgs a, int rowb) {
+  const Shape& s = a.s;
+  const int b = blockIdx.z;
+  if (!a.mask.active(b)) return;
+  const int* info = a.sc.evict_info + 2 * b;
+  const int first = info[0], n_new = info[1];
+  if (first >= n_new) return;
+  const int g = blockIdx.y >> 1;
+  char* pool = (char*)((blockIdx.y & 1) ? a.lv.Vd : a.lv.Kd) +
+               ((size_t)b * s.Hkv + g) * (size_t)s.cap * rowb + blockIdx.x * kSliceBytes;
+  const int32_t* map = a.sc.src_map + (size_t)b * s.cap;
+  constexpr int kLanesPerRow = kSliceBytes / 16;
+  constexpr int kRows = kMoveThreads / kLanesPerRow;
+  const int off = (threadIdx.x % kLanesPerRow) * 16;
+  const int r = threadIdx.x / kLanesPerRow;
+  for (int d0 = first; d0 < n_new; d0 += kRows * kMoveUnroll) {
+    uint4 v[kMoveUnroll];
+#pragma unroll
+    for (int u = 0; u < kMoveUnroll; ++u) {
+      const int d = d0 + u * kRows + r;
+      if (d < n_new) v[u] = *reinterpret_cast<const uint4*>(pool + (size_t)map[d] * rowb + off);
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // every source of this round has arrived
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kMoveUnroll; ++u) {
+      const int d = d0 + u * kRows + r;
+      if (d < n_new) *reinterpret_cast<uint4*>(pool + (size_t)d * rowb + off) = v[u];
+    }
+  }
+}
+
+// k, v [n_tokens, Hkv, D] (token-major) -> pool rows [row0, row0 + n_tokens) of every KV head of
+// sequence `seq` (head-major).  One 16-byte vector per thread.
+__global__ void ingest_kernel(char* Kpool, char* Vpool, const char* k, const char* v, int Hkv,
+                              int rowb, int rows_cap, int seq, int row0, int n_tokens) {
+  const int nv = rowb / 16;
+  const size_t total = (size_t)n_tokens * Hkv * nv;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const int vec = (int)(i % nv);
+    const size_t th = i / nv;
+    const int g = (int)(th % Hkv);
+    const size_t t = th / Hkv;
+    const size_t dst = (((size_t)seq * Hkv + g) * rows_cap + row0 + t) * rowb + vec * 16;
+    *reinterpret_cast<uint4*>(Kpool + dst) = *reinterpret_cast<const uint4*>(k + i * 16);
+    *reinterpret_cast<uint4*>(Vpool + dst) = *reinterpret_cast<const uint4*>(v + i * 16);
+  }
+}
+
+}  // namespace
+
+hipError_t configure_kernels() {
+  // the selection keeps scores + positions of one pool in LDS: up to 128 KiB of the CU's 160 KiB
+  return hipFuncSetAttribute((const void*)evict_select_kernel,
+                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                             kMaxDecodeCapacity * 8);
+}
+
+hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                        int threshold, hipStream_t st) {
+  EvictArgs a;
+  a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = threshold;
+  const size_t smem = (size_t)s.cap * 8;
+  hipLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rowb = s.D * (s.bf16 ? 2 : 4);
+  hipLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
+                     0, st, a, rowb);
+  return hipGetLastError();
+}
+
+hipError_t launch_ingest(const Shape& s, void* Kpool, void* Vpool, int rows_cap, int seq, int row0,
+                         const void* k, const void* v, int n_tokens, hipStream_t st) {
+  if (n_tokens <= 0) return hipSuccess;
+  const int rowb = s.D * (s.bf16 ? 2 : 4);
+  const size_t total = (size_t)n_tokens * s.Hkv * (rowb / 16);
+  const int threads = 256;
+  const int blocks = (int)((total + threads - 1) / threads < 65536 ? (total + threads - 1) / threads : 65536);
+  hipLaunchKernelGGL(ingest_kernel, dim3(blocks), dim3(threads), 0, st, (char*)Kpool, (char*)Vpool,
+                     (const char*)k, (const char*)v, s.Hkv, rowb, rows_cap, seq, row0, n_tokens);
+  return hipGetLastError();
+}
+
+}  // namespace mkv

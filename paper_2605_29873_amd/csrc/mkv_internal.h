@@ -1,0 +1,70 @@
+// Internal declarations shared by the library's own translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mkv {
+
+constexpr int kMaxBatch = 1024;          // sequences per layer (mask is passed by value)
+constexpr int kMaxDecodeCapacity = 16384;  // the selection kernel keeps one pool in LDS
+constexpr int kMaskWords = kMaxBatch / 64;
+
+// Which sequences take part in a launch; passed by value so a step needs no host->device copy.
+struct SeqMask {
+  uint64_t w[kMaskWords];
+  __host__ __device__ bool active(int b) const { return (w[b >> 6] >> (b & 63)) & 1ull; }
+};
+
+// Shapes and parameters of a context, by value to every kernel.
+struct Shape {
+  int B, H, Hkv, G, D, bf16;
+  int max_prefill;   // row capacity of the prefill pool per (seq, kv head)
+  int cap;           // row capacity of the decode pool per (seq, kv head)
+  int CH;            // keys per attention work-group (split size)
+  int S_max;         // split slots per sequence in the partial buffers
+  int budget, window;
+  float alpha;
+  float scale_log2;  // softmax scale * log2(e): logits are kept in base-2 units
+};
+
+// One layer's slice of the arena.  Pools are head-major: [B][Hkv][rows][D].
+struct LayerView {
+  void* Kp; void* Vp;      // prefill pool
+  void* Kd; void* Vd;      // decode pool
+  float* score;            // [B][cap]   importance vector I
+  int32_t* pos;            // [B][cap]   original decode position of each slot
+  int32_t* mlen;           // [B]        prefill length M
+  int32_t* nd;             // [B]        decode pool size before the step in flight
+  int32_t* nd_eff;         // [B]        decode pool size including the token appended in this step
+  int32_t* tpos;           // [B]        decode steps taken = position the next token gets
+};
+
+// Per-step scratch, shared by all layers (layers run one after another on one stream).
+struct Scratch {
+  float* part_o;      // [B][H][S_max][D]  un-normalised partial outputs per split
+  float* part_ml;     // [B][H][S_max][2]  (running max, running sum) per split, base-2 units
+  float* logits;      // [B][H][cap]       base-2 logits of decode keys
+  float* abar;        // [B][cap]          head-mean decode-slice attention of the last step
+  float* lse;         // [B][H]            base-2 log of the softmax normaliser of the last step
+  int32_t* src_map;   // [B][cap]          compaction map: new slot -> old slot
+  int32_t* evict_info;  // [B][2]          (first moved slot, new pool size) of the last selection
+};
+
+hipError_t launch_ingest(const Shape& s, void* Kpool, void* Vpool, int rows_cap, int seq, int row0,
+                         const void* k, const void* v, int n_tokens, hipStream_t st);
+
+hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, const void* q,
+                       const void* k_new, const void* v_new, const SeqMask& mask, int grid_splits,
+                       hipStream_t st);
+
+hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
+                         const SeqMask& mask, int max_nd_eff, hipStream_t st);
+
+// Evicts every masked sequence whose pool size exceeds `threshold` back to s.budget.
+hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                        int threshold, hipStream_t st);
+
+hipError_t configure_kernels();
+
+}  // namespace mkv

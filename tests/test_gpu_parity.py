@@ -1,0 +1,181 @@
+"""GPU parity: the HIP library against the CPU oracle on the same seeded inputs, through the C ABI.
+
+Small cases run every step in lock-step from an empty decode pool; the full-size configurations
+start from a synthetic mid-run pool just below the eviction trigger (so that a few dozen steps
+cross an eviction) and follow sampled sequences, in the launch configuration the bench uses."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import momentkv_oracle as O
+from paper_2605_29873_amd import inputs as X
+from tests.harness import Lockstep, make_ctx, to_device, from_device, oracle_state, OUT_TOL
+
+pytestmark = pytest.mark.gpu
+
+WL = X.workloads()
+
+
+def _run(ls, steps, t0=0, **kw):
+    try:
+        for t in range(t0, t0 + steps):
+            ls.step(t, **kw)
+        for s in ls.seqs:
+            ls.check_prefill_untouched(s)
+    finally:
+        ls.close()
+
+
+@pytest.mark.parametrize("split_keys", [0, 64])
+def test_cfg1_full_run_lockstep(mkv, split_keys):
+    # tiny fp32 layer, 200 steps, evict 9 whenever the pool exceeds 72; split 64 spans several
+    # work-groups and ragged tails in both segments
+    wl = WL["cfg1"]
+    ls = Lockstep(mkv, wl, split_keys=split_keys)
+    ls.prefill()
+    _run(ls, wl.steps, check_abar=True)
+    assert ls.evictions == 15          # steps 72, 81, ..., 198
+    print(f"cfg1 split={split_keys}: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}, "
+          f"{ls.evictions} evictions")
+
+
+def test_cfg2_llama_layer_crosses_an_eviction(mkv):
+    wl = WL["cfg2"]
+    ls = Lockstep(mkv, wl)
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 20, 3000)
+    _run(ls, 40, t0=3000, check_abar=True)
+    assert ls.evictions == 1
+    print(f"cfg2: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
+def test_cfg2_burst_window_from_empty_pool(mkv):
+    # the first 140 steps of the real run, short prefill to keep the oracle quick
+    wl = X.scaled(WL["cfg2"], prefill_min=700, prefill_max=700, decode_budget=96, evict_trigger=96 + 15,
+                  recent_window=16, burst_period=64, burst_keys=8, burst_len=6)
+    ls = Lockstep(mkv, wl, split_keys=128)
+    ls.prefill()
+    _run(ls, 140)
+    assert ls.evictions >= 2
+
+
+def test_cfg3_ragged_batch_full_size_sampled(mkv):
+    # all 16 ragged sequences on the GPU, three followed by the oracle
+    wl = WL["cfg3"]
+    ls = Lockstep(mkv, wl, seqs=[0, 7, 13], active=range(wl.batch))
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 3, 5000)
+    _run(ls, 6, t0=5000)
+    assert ls.evictions == 3
+    print(f"cfg3: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
+def test_cfg4_qwen_group7_evicts_every_step(mkv):
+    wl = WL["cfg4"]
+    ls = Lockstep(mkv, wl, seqs=[2, 5], active=range(wl.batch))
+    ls.prefill()
+    ls.load_snapshot(wl.decode_budget - 2, 9000)
+    _run(ls, 12, t0=9000)
+    assert ls.evictions == 2 * 10
+    print(f"cfg4: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
+def test_cfg5_shape_two_layers_sampled(mkv):
+    # cfg5's layer shape and pool sizes, at 2 layers x 4 sequences so that it loads in seconds;
+    # layer 1 is stepped, which exercises the per-layer arena offsets
+    wl = X.scaled(WL["cfg5"], n_layers=2, batch=4)
+    ls = Lockstep(mkv, wl, layer=1, seqs=[3], active=range(wl.batch))
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 1, 20000)
+    _run(ls, 3, t0=20000)
+    assert ls.evictions == 1
+
+
+@pytest.mark.parametrize("H,Hkv,D,dtype", [
+    (4, 4, 64, "bf16"),      # G = 1
+    (4, 2, 128, "f32"),      # G = 2, fp32 rows of 512 bytes
+    (6, 2, 128, "bf16"),     # G = 3: one masked head slot
+    (12, 2, 64, "f32"),      # G = 6 on the 7-wide kernel
+    (8, 1, 128, "bf16"),     # G = 8
+    (32, 2, 64, "bf16"),     # G = 16: two head passes per KV head
+])
+def test_head_layouts(mkv, H, Hkv, D, dtype):
+    wl = X.Workload("heads", batch=2, n_layers=1, n_q_heads=H, n_kv_heads=Hkv, head_dim=D, dtype=dtype,
+                    prefill_min=50, prefill_max=333, decode_budget=20, evict_trigger=27,
+                    recent_window=3, alpha=0.65, steps=60, hh_prob=0.05)
+    ls = Lockstep(mkv, wl, split_keys=64)
+    ls.prefill()
+    _run(ls, 60, check_abar=True)
+    assert ls.evictions >= 8
+
+
+@pytest.mark.parametrize("alpha,W,Bd,Te,M", [
+    (0.2, 0, 5, 5, 0),        # the paper's cadence, empty prefill
+    (0.98, 0, 1, 1, 3),       # budget of one
+    (1.0, 8, 8, 11, 17),      # cumulative scores; window = budget (pure sliding window)
+    (0.0, 2, 9, 40, 129),     # instantaneous scores, large chunk
+])
+def test_degenerate_parameters(mkv, alpha, W, Bd, Te, M):
+    wl = X.Workload("edge", batch=3, n_layers=1, n_q_heads=8, n_kv_heads=2, head_dim=64, dtype="f32",
+                    prefill_min=M, prefill_max=M, decode_budget=Bd, evict_trigger=Te,
+                    recent_window=W, alpha=alpha, steps=90, hh_prob=0.1)
+    ls = Lockstep(mkv, wl, split_keys=64)
+    ls.prefill()
+    _run(ls, 90, check_abar=True)
+    assert ls.evictions > 0
+
+
+def test_inactive_sequences_are_left_alone(mkv):
+    wl = X.scaled(WL["cfg1"], batch=3)
+    ls = Lockstep(mkv, wl, seqs=[0, 2])          # sequence 1 is never active
+    ls.prefill()
+    ls.out.fill_(7.0)
+    for t in range(30):
+        ls.step(t)
+    assert torch.all(ls.out[1] == 7.0)
+    assert mkv.mkv_get_lens(ls.ctx, 0, 1) == (0, 0, 0)
+    s, p = mkv.mkv_read_scores(ls.ctx, 0, 1)
+    assert s.size == 0
+    ls.close()
+
+
+def test_auto_eviction_matches_a_free_running_oracle(mkv):
+    # no score injection: the library's own trigger.  Retained sets must agree unless the cut fell
+    # on a near-tie (scores within the score tolerance of each other)
+    wl = WL["cfg1"]
+    ctx = make_ctx(mkv, wl, manual_evict=False)
+    st = oracle_state(wl)
+    k, v = X.prefill_kv(wl, 0, 0)
+    dk, dv = to_device(k, wl.dtype), to_device(v, wl.dtype)
+    mkv.mkv_prefill_append(ctx, 0, 0, dk.data_ptr(), dv.data_ptr(), k.shape[0])
+    st.prefill_append(k, v)
+    out = torch.empty((1, wl.n_q_heads, wl.head_dim), device="cuda")
+    near_ties = 0
+    for t in range(wl.steps):
+        q, kn, vn = X.step_batch(wl, 0, t)
+        dq, dkn, dvn = (to_device(a, wl.dtype) for a in (q, kn, vn))
+        mkv.mkv_decode_step(ctx, 0, dq.data_ptr(), dkn.data_ptr(), dvn.data_ptr(), out.data_ptr())
+        ref, _ = st.decode_step(q[0], kn[0], vn[0])
+        gs, gp = mkv.mkv_read_scores(ctx, 0, 0)
+        assert gs.size == st.n_decode <= wl.evict_trigger
+        assert np.all(np.diff(gp) > 0)
+        if not np.array_equal(gp, st.pos[0]):
+            only_gpu = set(gp.tolist()) - set(st.pos[0].tolist())
+            only_cpu = set(st.pos[0].tolist()) - set(gp.tolist())
+            a = np.array([gs[gp.tolist().index(p)] for p in only_gpu])
+            b = np.array([st.I[0][st.pos[0].tolist().index(p)] for p in only_cpu])
+            assert np.allclose(np.sort(a), np.sort(b), rtol=1e-3), "retained sets differ beyond a near-tie"
+            near_ties += 1
+            break
+        assert np.allclose(from_device(out)[0], ref, rtol=1e-4, atol=1e-5)
+    mkv.mkv_destroy(ctx)
+    print(f"free-running: {near_ties} near-tie divergences")
+
+
+def test_full_cache_run_needs_no_eviction(mkv):
+    # budget above the run length: plain attention over the growing cache ("Full Cache")
+    wl = X.scaled(WL["cfg1"], decode_budget=300, evict_trigger=300, recent_window=0, steps=120)
+    ls = Lockstep(mkv, wl)
+    ls.prefill()
+    _run(ls, 120)
+    assert ls.evictions == 0
