@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default cfg3: the HBM-bound Llama-3.1-8B-shaped layer)")
     ap.add_argument("--also", default="cfg2,cfg4,cfg5", help="comma list of further workloads reported under 'others' ('' = none)")
     ap.add_argument("--split-keys", type=int, default=0)
+    ap.add_argument("--attn-variant", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
@@ -53,7 +54,7 @@ class Job:
 
     BANK = 64
 
-    def __init__(self, wl, split_keys=0):
+    def __init__(self, wl, split_keys=0, variant=0):
         import torch
         import paper_2605_29873_amd.binding as mkv
         from paper_2605_29873_amd import inputs as X
@@ -65,7 +66,7 @@ class Job:
             head_dim=wl.head_dim, dtype=mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32,
             max_prefill=wl.prefill_max, decode_budget=wl.decode_budget, evict_trigger=wl.evict_trigger,
             decode_capacity=wl.capacity, recent_window=wl.recent_window, alpha=wl.alpha,
-            softmax_scale=0.0, score_mode=0, split_keys=split_keys,
+            softmax_scale=0.0, score_mode=0, split_keys=split_keys, attn_variant=variant,
             stream=torch.cuda.current_stream().cuda_stream)
         self.arena_bytes = mkv.mkv_required_bytes(cfg)
         self.ctx = mkv.mkv_create(cfg)
@@ -167,8 +168,8 @@ def time_region(job: Job, steps: int):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
-def measure(wl, steps, warmup, split_keys=0):
-    job = Job(wl, split_keys)
+def measure(wl, steps, warmup, split_keys=0, variant=0):
+    job = Job(wl, split_keys, variant)
     try:
         run_steps(job, warmup)
         # sizes the pools will have over the timed steps (deterministic: +1 per step, back to the
@@ -253,7 +254,7 @@ def main():
     mkv.load()
     wls = X.workloads()
     wl = wls[args.workload]
-    main_res = measure(wl, args.steps, args.warmup, args.split_keys)
+    main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant)
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w = wls[name]
@@ -262,7 +263,7 @@ def main():
         steps = args.steps if w.n_layers == 1 else max(chunk, 16)
         warm = args.warmup if w.n_layers == 1 else 8
         try:
-            others[name] = measure(w, steps, warm, args.split_keys)
+            others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant)
         except Exception as e:  # a side measurement must not lose the main line
             others[name] = {"error": repr(e)}
     line = {

@@ -32,7 +32,8 @@ class mkv_config(C.Structure):
                 ("max_prefill", C.c_int32), ("decode_budget", C.c_int32),
                 ("evict_trigger", C.c_int32), ("decode_capacity", C.c_int32),
                 ("recent_window", C.c_int32), ("alpha", C.c_float), ("softmax_scale", C.c_float),
-                ("score_mode", C.c_int32), ("split_keys", C.c_int32), ("stream", C.c_void_p),
+                ("score_mode", C.c_int32), ("split_keys", C.c_int32), ("attn_variant", C.c_int32),
+                ("stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
 
 
@@ -50,6 +51,9 @@ def load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; "
                            "g.build()'` first; there is no fallback path")
+    # torch first: the process must end up with ONE HIP runtime, the one torch brings, because the
+    # device memory and streams handed to the library come from torch
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
     lib.mkv_required_bytes.restype = C.c_size_t

@@ -13,8 +13,6 @@
 namespace mkv {
 namespace {
 
-constexpr int kWaves = 4;
-constexpr int kThreads = kWaves * 64;
 
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
@@ -110,16 +108,39 @@ struct AttnArgs {
   const char* k_new;
   const char* v_new;
   SeqMask mask;
-  int passes;  // ceil(G / GT): head passes per KV head
+  int passes;  // head passes per KV head: ceil(G / head lanes)
 };
 
+// quad_perm controls that exchange lane i with lane i^K inside every group of four lanes
+template <int K>
+__device__ __forceinline__ float quad_xor(float x) {
+  if constexpr (K == 1) return dpp_mov<0xB1>(x);       // [1,0,3,2]
+  else if constexpr (K == 2) return dpp_mov<0x4E>(x);  // [2,3,0,1]
+  else if constexpr (K == 3) return dpp_mov<0x1B>(x);  // [3,2,1,0]
+  else return x;
+}
+
 // Work-group (split, kv head x pass, seq): streams keys [j0, jn) of one segment (prefill or
-// decode) of one KV head, for up to GT of its query heads, and leaves an un-normalised partial
-// (max, sum, sum p*V) per head.  Lane layout: LPK adjacent lanes share a key, lane c of a group
-// holding the 16-byte vectors c, c+LPK, ... of the row, so one load instruction of a wave reads
-// 64/LPK rows x (LPK*16) contiguous bytes.
-template <bool BF16, int D, int GT, int LPK, int IT>
-__global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) {
+// decode) of one KV head, for up to HL of its query heads, and leaves an un-normalised partial
+// (reference, sum, sum p*V) per head.
+//
+// Lane layout.  LPK adjacent lanes share a key; lane c of a group holds the 16-byte vectors
+// c, c+LPK, ... of the row, so one load instruction of a wave reads 64/LPK rows x (LPK*16)
+// contiguous bytes.  Inside a key group, lane c is additionally the OWNER of head "hm" = c mod HL:
+//   - every lane forms partial dot products for all HL heads, stored relative to its own head
+//     (x[k] belongs to head hm^k), so that a log2(HL)-stage reduce-scatter over DPP lane exchanges
+//     leaves each lane with the full logit of its own head only: HL-1 + log2(LPK/HL) adds per
+//     key instead of HL*log2(LPK);
+//   - the softmax (max tracking, exp2, running sum) is done once per (key, head) by the owner
+//     lanes instead of LPK times;
+//   - for p*V each lane needs the probabilities of all HL heads: they are fetched from the owner
+//     lanes with quad_perm DPP reads (plus one half-row mirror when HL = 8).
+// With HL = 8 the three exchanges are "xor 7" (row_half_mirror), xor 2 and xor 1, which span the
+// eight lanes; head numbers are the lane's coordinates in that basis.
+template <bool BF16, int D, int HL, int LPK, int IT, int WPB, bool PF, bool DIAG = false>
+__global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) {
+  constexpr int kWaves = WPB;
+  constexpr int kThreads = WPB * 64;
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int ROWB = D * ES;
   constexpr int NV = ROWB / 16;
@@ -128,6 +149,8 @@ __global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) 
   constexpr int KPW = 64 / LPK;
   constexpr int TK = KPW * IT;
   static_assert(NV % LPK == 0 && VPL >= 1, "row must split evenly over the lane group");
+  static_assert(HL == 1 || HL == 2 || HL == 4 || HL == 8, "head lanes");
+  static_assert(LPK % HL == 0 && (LPK == 16 || LPK == 8), "lane group");
 
   const Shape& s = a.s;
   const int b = blockIdx.z;
@@ -153,8 +176,17 @@ __global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) 
   const int c = lane % LPK;
   const int kg = lane / LPK;
 
+  // head owned by this lane, as coordinates in the exchange basis (see above)
+  int hm;
+  if constexpr (HL == 8) {
+    const int i = c & 7, hi = i >> 2;
+    hm = (hi << 2) | ((((i >> 1) & 1) ^ hi) << 1) | ((i & 1) ^ hi);
+  } else {
+    hm = c & (HL - 1);
+  }
+
   const size_t head_row = (size_t)b * s.Hkv + g;
-  const size_t pool_rows = dec ? (size_t)s.cap : (size_t)s.max_prefill;
+  const size_t pool_rows = dec ? (size_t)s.dstride : (size_t)s.pstride;
   const char* kbase = (const char*)(dec ? a.lv.Kd : a.lv.Kp) + head_row * pool_rows * ROWB;
   const char* vbase = (const char*)(dec ? a.lv.Vd : a.lv.Vp) + head_row * pool_rows * ROWB;
   const char* knew = a.k_new + head_row * ROWB;
@@ -171,30 +203,30 @@ __global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) 
     *reinterpret_cast<uint4*>(dst) = ldg16(src);
   }
 
-  // queries of this pass, in storage form, at this lane's vector positions
-  uint4 qv[GT][VPL];
-  int hq[GT];
+  // queries in storage form at this lane's vector positions; qv[k] belongs to head hm ^ k
+  uint4 qv[HL][VPL];
 #pragma unroll
-  for (int h = 0; h < GT; ++h) {
-    const int hl = pass * GT + h;
-    hq[h] = (hl < s.G) ? g * s.G + hl : -1;
+  for (int k = 0; k < HL; ++k) {
+    const int hl = pass * HL + (hm ^ k);
 #pragma unroll
     for (int vi = 0; vi < VPL; ++vi) {
-      qv[h][vi] = (hq[h] >= 0) ? ldg16(a.q + ((size_t)b * s.H + hq[h]) * ROWB + (vi * LPK + c) * 16)
-                               : make_uint4(0, 0, 0, 0);
+      qv[k][vi] = (hl < s.G) ? ldg16(a.q + ((size_t)b * s.H + g * s.G + hl) * ROWB + (vi * LPK + c) * 16)
+                             : make_uint4(0, 0, 0, 0);
     }
   }
+  const int h_own = pass * HL + hm;                    // head within the KV group
+  const bool own_valid = h_own < s.G;
+  float* const logit_row = a.sc.logits + ((size_t)b * s.H + g * s.G + (own_valid ? h_own : 0)) * s.cap;
+  const bool stash = dec && own_valid && c < HL;       // first owner lane of each head writes
 
-  float m[GT], l[GT], acc[GT][VPL][EPV];
+  float m_own = -INFINITY, l_own = 0.f;
+  float acc[HL][VPL][EPV];                             // acc[k] belongs to head hm ^ k
 #pragma unroll
-  for (int h = 0; h < GT; ++h) {
-    m[h] = -INFINITY;
-    l[h] = 0.f;
+  for (int k = 0; k < HL; ++k)
 #pragma unroll
     for (int vi = 0; vi < VPL; ++vi)
 #pragma unroll
-      for (int e = 0; e < EPV; ++e) acc[h][vi][e] = 0.f;
-  }
+      for (int e = 0; e < EPV; ++e) acc[k][vi][e] = 0.f;
 
   const int ntile = (jn - j0 + TK - 1) / TK;
 
@@ -214,97 +246,187 @@ __global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) 
     }
   };
 
-  uint4 kr[IT][VPL], vr[IT][VPL];
-  if (wave < ntile) load_tile(wave, kr, vr);
-
-  for (int tt = wave; tt < ntile; tt += kWaves) {
-    uint4 kn[IT][VPL], vn[IT][VPL];
-    const bool more = tt + kWaves < ntile;
-    if (more) load_tile(tt + kWaves, kn, vn);  // prefetch: in flight during this tile's math
-
-    const int jb = j0 + tt * TK;
-    float sc[IT][GT];
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-      const int j = jb + it * KPW + kg;
-#pragma unroll
-      for (int h = 0; h < GT; ++h) {
-        float d = 0.f;
-#pragma unroll
-        for (int vi = 0; vi < VPL; ++vi) d = dot_vec<BF16>(kr[it][vi], qv[h][vi], d);
-        d = group_sum<LPK>(d) * s.scale_log2;
-        sc[it][h] = (j < jn) ? d : -INFINITY;
-      }
-      if (dec && c == 0 && j < jn) {
-#pragma unroll
-        for (int h = 0; h < GT; ++h)
-          if (hq[h] >= 0) a.sc.logits[((size_t)b * s.H + hq[h]) * s.cap + j] = sc[it][h];
-      }
-    }
-
-    // online softmax, one rescale per tile (skipped when the running max did not move)
-#pragma unroll
-    for (int h = 0; h < GT; ++h) {
-      float tm = sc[0][h];
-#pragma unroll
-      for (int it = 1; it < IT; ++it) tm = fmaxf(tm, sc[it][h]);
-      tm = across_groups_max<LPK>(tm);
-      if (tm > m[h]) {
-        const float cf = fast_exp2(m[h] - tm);
-        l[h] *= cf;
-#pragma unroll
-        for (int vi = 0; vi < VPL; ++vi)
-#pragma unroll
-          for (int e = 0; e < EPV; ++e) acc[h][vi][e] *= cf;
-        m[h] = tm;
-      }
-    }
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-#pragma unroll
-      for (int h = 0; h < GT; ++h) {
-        const float p = fast_exp2(sc[it][h] - m[h]);
-        l[h] += p;
-#pragma unroll
-        for (int vi = 0; vi < VPL; ++vi) axpy_vec<BF16>(p, vr[it][vi], acc[h][vi]);
-      }
-    }
-
-    if (more) {
+  // One tile: logits of IT keys per lane group, softmax update by the owner lanes, value
+  // accumulation.  Each owner lane keeps its own running reference m_own, raised only when a
+  // tile's maximum exceeds it by more than kSlack (base-2 units): exp2(s - m) then stays below
+  // 2^kSlack, far from overflow, and the rescale is rare.  Lane groups are merged after the loop.
+  constexpr float kSlack = 8.0f;
+  auto compute_tile = [&](int tt, const uint4 (&kr)[IT][VPL], const uint4 (&vr)[IT][VPL]) {
+    if constexpr (DIAG) {  // tuning aid: memory stream only, no attention math (results are garbage)
+      uint32_t x = 0;
 #pragma unroll
       for (int it = 0; it < IT; ++it)
 #pragma unroll
-        for (int vi = 0; vi < VPL; ++vi) {
-          kr[it][vi] = kn[it][vi];
-          vr[it][vi] = vn[it][vi];
-        }
+        for (int vi = 0; vi < VPL; ++vi)
+          x ^= kr[it][vi].x ^ kr[it][vi].y ^ kr[it][vi].z ^ kr[it][vi].w ^ vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w;
+      l_own += as_f(x & 0x3f800000u);
+      return;
+    }
+    const int jb = j0 + tt * TK;
+    float sc[IT];
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      const int j = jb + it * KPW + kg;
+      float x[HL];
+#pragma unroll
+      for (int k = 0; k < HL; ++k) {
+        float d = 0.f;
+#pragma unroll
+        for (int vi = 0; vi < VPL; ++vi) d = dot_vec<BF16>(kr[it][vi], qv[k][vi], d);
+        x[k] = d;
+      }
+      // reduce-scatter over the HL lanes that own the heads ...
+      if constexpr (HL == 8) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) x[k] += dpp_mov<kDppHalfMirror>(x[k ^ 4]);
+      }
+      if constexpr (HL >= 4) {
+#pragma unroll
+        for (int k = 0; k < 2; ++k) x[k] += quad_xor<2>(x[k ^ 2]);
+      }
+      if constexpr (HL >= 2) x[0] += quad_xor<1>(x[1]);
+      // ... then over the LPK/HL lane sets of the key group (same owner position in each)
+      float d = x[0];
+      if constexpr (LPK == 16) {
+        if constexpr (HL <= 1) d += dpp_mov<kDppRowRor + 1>(d);
+        if constexpr (HL <= 2) d += dpp_mov<kDppRowRor + 2>(d);
+        if constexpr (HL <= 4) d += dpp_mov<kDppRowRor + 4>(d);
+        d += dpp_mov<kDppRowRor + 8>(d);
+      } else {  // 8 lanes per key: two keys share a 16-lane row, so rotations would mix keys
+        if constexpr (HL <= 1) d += quad_xor<1>(d);
+        if constexpr (HL <= 2) d += quad_xor<2>(d);
+        if constexpr (HL <= 4) d += __shfl_xor(d, 4);
+      }
+      d *= s.scale_log2;
+      sc[it] = (j < jn) ? d : -INFINITY;
+      if (stash && j < jn) logit_row[j] = d;
+    }
+    float tm = sc[0];
+#pragma unroll
+    for (int it = 1; it < IT; ++it) tm = fmaxf(tm, sc[it]);
+    const bool up = tm > m_own + kSlack;   // also true for the first finite score (m = -inf)
+    if (__any(up)) {
+      const float mn = up ? tm : m_own;
+      const float cf = up ? fast_exp2(m_own - mn) : 1.0f;   // exp2(-inf) = 0 on the first raise
+      float cf_o = 0.f;
+      if constexpr (HL == 8) cf_o = dpp_mov<kDppHalfMirror>(cf);
+      l_own *= cf;
+      m_own = mn;
+      // per-head factors, fetched from the owner lanes
+      float cfs[HL];
+      cfs[0] = cf;
+      if constexpr (HL >= 2) cfs[1] = quad_xor<1>(cf);
+      if constexpr (HL >= 4) { cfs[2] = quad_xor<2>(cf); cfs[3] = quad_xor<3>(cf); }
+      if constexpr (HL == 8) {
+        cfs[4] = cf_o; cfs[5] = quad_xor<1>(cf_o); cfs[6] = quad_xor<2>(cf_o); cfs[7] = quad_xor<3>(cf_o);
+      }
+#pragma unroll
+      for (int k = 0; k < HL; ++k)
+#pragma unroll
+        for (int vi = 0; vi < VPL; ++vi)
+#pragma unroll
+          for (int e = 0; e < EPV; ++e) acc[k][vi][e] *= cfs[k];
+    }
+#pragma unroll
+    for (int it = 0; it < IT; ++it) {
+      // a lane set that has seen no key yet has m = -inf and only masked scores: guard exp2(nan)
+      const float p = (sc[it] == -INFINITY) ? 0.f : fast_exp2(sc[it] - m_own);
+      l_own += p;
+      float ps[HL];
+      ps[0] = p;
+      if constexpr (HL >= 2) ps[1] = quad_xor<1>(p);
+      if constexpr (HL >= 4) { ps[2] = quad_xor<2>(p); ps[3] = quad_xor<3>(p); }
+      if constexpr (HL == 8) {
+        const float po = dpp_mov<kDppHalfMirror>(p);
+        ps[4] = po; ps[5] = quad_xor<1>(po); ps[6] = quad_xor<2>(po); ps[7] = quad_xor<3>(po);
+      }
+#pragma unroll
+      for (int k = 0; k < HL; ++k)
+#pragma unroll
+        for (int vi = 0; vi < VPL; ++vi) axpy_vec<BF16>(ps[k], vr[it][vi], acc[k][vi]);
+    }
+  };
+
+  if constexpr (PF) {
+    // two register buffers, loop unrolled by two so that the prefetch needs no register copies
+    uint4 ka[IT][VPL], va[IT][VPL], kb[IT][VPL], vb[IT][VPL];
+    if (wave < ntile) load_tile(wave, ka, va);
+    for (int tt = wave; tt < ntile; tt += 2 * kWaves) {
+      if (tt + kWaves < ntile) load_tile(tt + kWaves, kb, vb);
+      compute_tile(tt, ka, va);
+      if (tt + kWaves >= ntile) break;
+      if (tt + 2 * kWaves < ntile) load_tile(tt + 2 * kWaves, ka, va);
+      compute_tile(tt + kWaves, kb, vb);
+    }
+  } else {
+    // no software prefetch: the other waves of the SIMD cover the load latency
+    for (int tt = wave; tt < ntile; tt += kWaves) {
+      uint4 ka[IT][VPL], va[IT][VPL];
+      load_tile(tt, ka, va);
+      compute_tile(tt, ka, va);
     }
   }
 
+  // merge the lane sets of the wave: common reference per head, then sums across key groups
+  // (and across the LPK/HL owner sets inside a key group for the running sum)
+  {
+    float mw = m_own;
+    if constexpr (LPK == 16) {
+      if constexpr (HL <= 1) mw = fmaxf(mw, dpp_mov<kDppRowRor + 1>(mw));
+      if constexpr (HL <= 2) mw = fmaxf(mw, dpp_mov<kDppRowRor + 2>(mw));
+      if constexpr (HL <= 4) mw = fmaxf(mw, dpp_mov<kDppRowRor + 4>(mw));
+      mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
+    } else {
+      if constexpr (HL <= 1) mw = fmaxf(mw, quad_xor<1>(mw));
+      if constexpr (HL <= 2) mw = fmaxf(mw, quad_xor<2>(mw));
+      if constexpr (HL <= 4) mw = fmaxf(mw, __shfl_xor(mw, 4));
+      mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
+    }
+    mw = fmaxf(mw, __shfl_xor(mw, 16));
+    mw = fmaxf(mw, __shfl_xor(mw, 32));
+    // every owner set of a head saw the same keys, so their m_own and l_own are identical copies:
+    // only the key groups differ.  Scale to the wave's reference and add up the key groups.
+    const float cf = (m_own == -INFINITY) ? 0.f : fast_exp2(m_own - mw);
+    float cf_o = 0.f;
+    if constexpr (HL == 8) cf_o = dpp_mov<kDppHalfMirror>(cf);
+    float cfs[HL];
+    cfs[0] = cf;
+    if constexpr (HL >= 2) cfs[1] = quad_xor<1>(cf);
+    if constexpr (HL >= 4) { cfs[2] = quad_xor<2>(cf); cfs[3] = quad_xor<3>(cf); }
+    if constexpr (HL == 8) {
+      cfs[4] = cf_o; cfs[5] = quad_xor<1>(cf_o); cfs[6] = quad_xor<2>(cf_o); cfs[7] = quad_xor<3>(cf_o);
+    }
+    l_own = across_groups_sum<LPK>(l_own * cf);
+    m_own = mw;
+#pragma unroll
+    for (int k = 0; k < HL; ++k)
+#pragma unroll
+      for (int vi = 0; vi < VPL; ++vi)
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[k][vi][e] = across_groups_sum<LPK>(acc[k][vi][e] * cfs[k]);
+  }
+
   // wave partial -> LDS -> work-group partial
-  __shared__ float sm_acc[kWaves][GT][D];
-  __shared__ float sm_m[kWaves][GT];
-  __shared__ float sm_l[kWaves][GT];
+  __shared__ float sm_acc[kWaves][HL][D];
+  __shared__ float sm_m[kWaves][HL];
+  __shared__ float sm_l[kWaves][HL];
+  if (kg == 0) {
 #pragma unroll
-  for (int h = 0; h < GT; ++h) {
-    l[h] = across_groups_sum<LPK>(l[h]);
+    for (int k = 0; k < HL; ++k)
 #pragma unroll
-    for (int vi = 0; vi < VPL; ++vi)
+      for (int vi = 0; vi < VPL; ++vi)
 #pragma unroll
-      for (int e = 0; e < EPV; ++e) {
-        const float v = across_groups_sum<LPK>(acc[h][vi][e]);
-        if (kg == 0) sm_acc[wave][h][(vi * LPK + c) * EPV + e] = v;
-      }
-    if (lane == 0) {
-      sm_m[wave][h] = m[h];
-      sm_l[wave][h] = l[h];
+        for (int e = 0; e < EPV; ++e) sm_acc[wave][hm ^ k][(vi * LPK + c) * EPV + e] = acc[k][vi][e];
+    if (c < HL) {
+      sm_m[wave][hm] = m_own;
+      sm_l[wave][hm] = l_own;
     }
   }
   __syncthreads();
 
-  for (int idx = tid; idx < GT * D; idx += kThreads) {
+  for (int idx = tid; idx < HL * D; idx += kThreads) {
     const int h = idx / D, d = idx - h * D;
-    const int hl = pass * GT + h;
+    const int hl = pass * HL + h;
     if (hl >= s.G) continue;
     float mx = sm_m[0][h];
 #pragma unroll
@@ -312,7 +434,7 @@ __global__ __launch_bounds__(kThreads) void attn_split_kernel(const AttnArgs a) 
     float o = 0.f, lt = 0.f;
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
-      const float wgt = fast_exp2(sm_m[w][h] - mx);  // a wave without tiles has max -inf -> 0
+      const float wgt = fast_exp2(sm_m[w][h] - mx);  // a wave without tiles has reference -inf -> 0
       o = fmaf(wgt, sm_acc[w][h][d], o);
       lt = fmaf(wgt, sm_l[w][h], lt);
     }
@@ -346,6 +468,28 @@ constexpr int kFinishThreads = 256;
 // Att_t (Eq. 2).  The other blocks own 256 decode slots each: they rebuild every head's softmax
 // normaliser from the split (max, sum) pairs, turn the stashed logits into probabilities, take the
 // head mean (Eq. 4) and apply I <- alpha*I + abar (Eq. 5), with I = 0 for the new slot (Eq. 6).
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
+  return x;
+}
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
+  return x;
+}
+
+// Softmax normaliser of one head from its split (reference, sum) pairs, by one whole wave:
+// returns the common reference mx and the total sum L relative to it (both base 2).
+__device__ __forceinline__ void wave_merge_ml(const float* ml, int ns, int lane, float& mx, float& L) {
+  float m_loc = -INFINITY;
+  for (int i = lane; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[2 * i]);
+  mx = wave_max(m_loc);
+  float l_loc = 0.f;
+  for (int i = lane; i < ns; i += 64) l_loc = fmaf(fast_exp2(ml[2 * i] - mx), ml[2 * i + 1], l_loc);
+  L = wave_sum(l_loc);
+}
+
 template <int D>
 __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs a) {
   const Shape& s = a.s;
@@ -355,7 +499,8 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   const int n1 = a.lv.nd_eff[b];
   const int n0 = n1 - 1;
   const int ns = (M + s.CH - 1) / s.CH + (n1 + s.CH - 1) / s.CH;
-  const int tid = threadIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  extern __shared__ float smem[];  // head blocks: [S_max] split weights; slot blocks: [H] normalisers
 
   if ((int)blockIdx.x < s.H) {
     const int h = blockIdx.x;
@@ -363,16 +508,23 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
     const int d = tid % D, sub = tid / D;
     const size_t slot0 = ((size_t)b * s.H + h) * s.S_max;
     const float* ml = a.sc.part_ml + slot0 * 2;
-    float mx = -INFINITY;
-    for (int i = 0; i < ns; ++i) mx = fmaxf(mx, ml[2 * i]);
-    float L = 0.f, o = 0.f;
-    for (int i = 0; i < ns; ++i) L = fmaf(fast_exp2(ml[2 * i] - mx), ml[2 * i + 1], L);
-    for (int i = sub; i < ns; i += SUB)
-      o = fmaf(fast_exp2(ml[2 * i] - mx), a.sc.part_o[(slot0 + i) * D + d], o);
+    float mx, L;
+    wave_merge_ml(ml, ns, lane, mx, L);        // every wave computes the same pair
+    for (int i = tid; i < ns; i += kFinishThreads) smem[i] = fast_exp2(ml[2 * i] - mx);
+    __syncthreads();
+    float o0 = 0.f, o1 = 0.f;
+    const float* po = a.sc.part_o + slot0 * D + d;
+    int i = sub;
+    for (; i + SUB < ns; i += 2 * SUB) {       // two independent loads in flight
+      o0 = fmaf(smem[i], po[(size_t)i * D], o0);
+      o1 = fmaf(smem[i + SUB], po[(size_t)(i + SUB) * D], o1);
+    }
+    if (i < ns) o0 = fmaf(smem[i], po[(size_t)i * D], o0);
     __shared__ float red[kFinishThreads];
-    red[tid] = o;
+    red[tid] = o0 + o1;
     __syncthreads();
     if (sub == 0) {
+      float o = red[d];
 #pragma unroll
       for (int k = 1; k < SUB; ++k) o += red[k * D + d];
       const float r = o / L;
@@ -389,22 +541,23 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
 
   const int jb = ((int)blockIdx.x - s.H) * kFinishThreads;
   if (jb >= n1) return;
-  extern __shared__ float sm_lse[];  // [H]
-  for (int h = tid; h < s.H; h += kFinishThreads) {
-    const float* ml = a.sc.part_ml + ((size_t)b * s.H + h) * s.S_max * 2;
-    float mx = -INFINITY;
-    for (int i = 0; i < ns; ++i) mx = fmaxf(mx, ml[2 * i]);
-    float L = 0.f;
-    for (int i = 0; i < ns; ++i) L = fmaf(fast_exp2(ml[2 * i] - mx), ml[2 * i + 1], L);
-    sm_lse[h] = mx + log2f(L);
+  for (int h = wave; h < s.H; h += kFinishThreads / 64) {
+    float mx, L;
+    wave_merge_ml(a.sc.part_ml + ((size_t)b * s.H + h) * s.S_max * 2, ns, lane, mx, L);
+    if (lane == 0) smem[h] = mx + log2f(L);
   }
   __syncthreads();
   const int j = jb + tid;
   if (j >= n1) return;
-  float sum = 0.f;
+  float sum0 = 0.f, sum1 = 0.f;
   const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
-  for (int h = 0; h < s.H; ++h) sum += fast_exp2(lg[(size_t)h * s.cap] - sm_lse[h]);
-  const float abar = sum * a.inv_H;
+  int h = 0;
+  for (; h + 1 < s.H; h += 2) {
+    sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
+    sum1 += fast_exp2(lg[(size_t)(h + 1) * s.cap] - smem[h + 1]);
+  }
+  if (h < s.H) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
+  const float abar = (sum0 + sum1) * a.inv_H;
   const size_t si = (size_t)b * s.cap + j;
   const float prev = (j == n0) ? 0.f : a.lv.score[si];
   a.lv.score[si] = fmaf(s.alpha, prev, abar);
@@ -416,28 +569,49 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   }
 }
 
-template <bool BF16, int D, int GT>
-hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
-  // lanes per key / keys per lane per tile: chosen to keep the register count near 128
-  constexpr int ROWB = D * (BF16 ? 2 : 4);
-  constexpr int LPK = (ROWB / 16 >= 16) ? 16 : ROWB / 16;
-  constexpr int IT = 4;
-  hipLaunchKernelGGL((attn_split_kernel<BF16, D, GT, LPK, IT>), grid, dim3(kThreads), 0, st, a);
+template <bool BF16, int D, int HL, int IT, int WPB, bool PF, bool DIAG = false>
+hipError_t launch_attn_v(const AttnArgs& a, dim3 grid, hipStream_t st) {
+  constexpr int NV = D * (BF16 ? 2 : 4) / 16;
+  constexpr int LPK = NV < 16 ? NV : 16;
+  hipLaunchKernelGGL((attn_split_kernel<BF16, D, HL, LPK, IT, WPB, PF, DIAG>), grid, dim3(WPB * 64), 0, st, a);
   return hipGetLastError();
+}
+
+// Tile depth, work-group size and prefetch.  Variant 0 is the tuned default; the others exist for
+// tuning runs on the Llama/Qwen-shaped bf16 kernels only.
+template <bool BF16, int D, int HL>
+hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
+  if constexpr (BF16 && D == 128 && (HL == 4 || HL == 8)) {
+    switch (a.s.variant) {
+      case 1: return launch_attn_v<BF16, D, HL, 4, 4, true>(a, grid, st);
+      case 2: return launch_attn_v<BF16, D, HL, 2, 4, true>(a, grid, st);
+      case 3: return launch_attn_v<BF16, D, HL, 4, 4, false>(a, grid, st);
+      case 4: return launch_attn_v<BF16, D, HL, 2, 4, false>(a, grid, st);
+      case 5: return launch_attn_v<BF16, D, HL, 8, 4, false>(a, grid, st);
+      case 6: return launch_attn_v<BF16, D, HL, 8, 4, true>(a, grid, st);
+      case 7: return launch_attn_v<BF16, D, HL, 4, 8, true>(a, grid, st);
+      case 8: return launch_attn_v<BF16, D, HL, 2, 8, true>(a, grid, st);
+      case 9: return launch_attn_v<BF16, D, HL, 4, 2, true>(a, grid, st);
+      case 10: return launch_attn_v<BF16, D, HL, 4, 4, true, true>(a, grid, st);
+      case 11: return launch_attn_v<BF16, D, HL, 4, 4, false, true>(a, grid, st);
+      case 12: return launch_attn_v<BF16, D, HL, 8, 4, false, true>(a, grid, st);
+      default: break;
+    }
+  }
+  return launch_attn_v<BF16, D, HL, 4, 4, true>(a, grid, st);
 }
 
 template <bool BF16, int D>
 hipError_t launch_attn_d(const AttnArgs& a0, hipStream_t st, int grid_splits) {
   AttnArgs a = a0;
   const int G = a.s.G;
-  const int gt = (G == 1) ? 1 : (G == 2) ? 2 : (G <= 4) ? 4 : (G <= 7) ? 7 : 8;
-  a.passes = (G + gt - 1) / gt;
+  const int hl = (G == 1) ? 1 : (G == 2) ? 2 : (G <= 4) ? 4 : 8;  // head lanes per key group
+  a.passes = (G + hl - 1) / hl;
   dim3 grid(grid_splits, a.s.Hkv * a.passes, a.s.B);
-  switch (gt) {
+  switch (hl) {
     case 1: return launch_attn_t<BF16, D, 1>(a, grid, st);
     case 2: return launch_attn_t<BF16, D, 2>(a, grid, st);
     case 4: return launch_attn_t<BF16, D, 4>(a, grid, st);
-    case 7: return launch_attn_t<BF16, D, 7>(a, grid, st);
     default: return launch_attn_t<BF16, D, 8>(a, grid, st);
   }
 }
@@ -460,7 +634,7 @@ hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc,
   FinishArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.inv_H = 1.0f / (float)s.H;
   dim3 grid(s.H + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
-  const size_t smem = (size_t)s.H * sizeof(float);
+  const size_t smem = (size_t)(s.H > s.S_max ? s.H : s.S_max) * sizeof(float);
   if (s.D == 128) hipLaunchKernelGGL((finish_kernel<128>), grid, dim3(kFinishThreads), smem, st, a);
   else hipLaunchKernelGGL((finish_kernel<64>), grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();

@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArg
   if (first >= n_new) return;
   const int g = blockIdx.y >> 1;
   char* pool = (char*)((blockIdx.y & 1) ? a.lv.Vd : a.lv.Kd) +
-               ((size_t)b * s.Hkv + g) * (size_t)s.cap * rowb + blockIdx.x * kSliceBytes;
+               ((size_t)b * s.Hkv + g) * (size_t)s.dstride * rowb + blockIdx.x * kSliceBytes;
   const int32_t* map = a.sc.src_map + (size_t)b * s.cap;
   constexpr int kLanesPerRow = kSliceBytes / 16;
   constexpr int kRows = kMoveThreads / kLanesPerRow;

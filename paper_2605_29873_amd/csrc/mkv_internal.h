@@ -21,9 +21,12 @@ struct Shape {
   int B, H, Hkv, G, D, bf16;
   int max_prefill;   // row capacity of the prefill pool per (seq, kv head)
   int cap;           // row capacity of the decode pool per (seq, kv head)
+  int pstride;       // rows between consecutive (seq, kv head) regions of the prefill pool
+  int dstride;       // same for the decode pool (>= cap; padded, see the arena layout)
   int CH;            // keys per attention work-group (split size)
   int S_max;         // split slots per sequence in the partial buffers
   int budget, window;
+  int variant;       // attention kernel variant (tuning), 0 = default
   float alpha;
   float scale_log2;  // softmax scale * log2(e): logits are kept in base-2 units
 };
