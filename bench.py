@@ -37,6 +37,7 @@ def parse_args():
     ap.add_argument("--also", default="cfg2,cfg4,cfg5", help="comma list of further workloads reported under 'others' ('' = none)")
     ap.add_argument("--split-keys", type=int, default=0)
     ap.add_argument("--attn-variant", type=int, default=0)
+    ap.add_argument("--groups-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
@@ -54,7 +55,7 @@ class Job:
 
     BANK = 64
 
-    def __init__(self, wl, split_keys=0, variant=0):
+    def __init__(self, wl, split_keys=0, variant=0, gpc=0):
         import torch
         import paper_2605_29873_amd.binding as mkv
         from paper_2605_29873_amd import inputs as X
@@ -66,7 +67,7 @@ class Job:
             head_dim=wl.head_dim, dtype=mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32,
             max_prefill=wl.prefill_max, decode_budget=wl.decode_budget, evict_trigger=wl.evict_trigger,
             decode_capacity=wl.capacity, recent_window=wl.recent_window, alpha=wl.alpha,
-            softmax_scale=0.0, score_mode=0, split_keys=split_keys, attn_variant=variant,
+            softmax_scale=0.0, score_mode=0, split_keys=split_keys, attn_variant=variant, groups_per_cu=gpc,
             stream=torch.cuda.current_stream().cuda_stream)
         self.arena_bytes = mkv.mkv_required_bytes(cfg)
         self.ctx = mkv.mkv_create(cfg)
@@ -168,8 +169,8 @@ def time_region(job: Job, steps: int):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
-def measure(wl, steps, warmup, split_keys=0, variant=0):
-    job = Job(wl, split_keys, variant)
+def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0):
+    job = Job(wl, split_keys, variant, gpc)
     try:
         run_steps(job, warmup)
         # sizes the pools will have over the timed steps (deterministic: +1 per step, back to the
@@ -254,7 +255,7 @@ def main():
     mkv.load()
     wls = X.workloads()
     wl = wls[args.workload]
-    main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant)
+    main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant, args.groups_per_cu)
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w = wls[name]
@@ -263,7 +264,7 @@ def main():
         steps = args.steps if w.n_layers == 1 else max(chunk, 16)
         warm = args.warmup if w.n_layers == 1 else 8
         try:
-            others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant)
+            others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant, args.groups_per_cu)
         except Exception as e:  # a side measurement must not lose the main line
             others[name] = {"error": repr(e)}
     line = {

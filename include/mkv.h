@@ -73,9 +73,11 @@ typedef struct {
   float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
   float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
   int32_t score_mode;      /* mkv_score_mode                                                     */
-  int32_t split_keys;      /* tuning: keys per attention work-group (multiple of 64);
-                              0 => chosen from the shapes                                      */
+  int32_t split_keys;      /* tuning: keys per attention work-group (multiple of 64); 0 => chosen
+                              per step so that the launch just fills the chip                   */
   int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default             */
+  int32_t groups_per_cu;   /* tuning: attention work-groups per compute unit a launch aims for;
+                              0 => library default                                              */
   void*   stream;          /* hipStream_t, borrowed; NULL => the default stream                  */
   void*   arena;           /* optional device pointer, 256-byte aligned, caller-owned, must outlive
                               the context; NULL => the library allocates and frees              */

@@ -33,6 +33,7 @@ class mkv_config(C.Structure):
                 ("evict_trigger", C.c_int32), ("decode_capacity", C.c_int32),
                 ("recent_window", C.c_int32), ("alpha", C.c_float), ("softmax_scale", C.c_float),
                 ("score_mode", C.c_int32), ("split_keys", C.c_int32), ("attn_variant", C.c_int32),
+                ("groups_per_cu", C.c_int32),
                 ("stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
 

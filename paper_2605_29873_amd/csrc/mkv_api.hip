@@ -19,15 +19,8 @@ using namespace mkv;
 namespace {
 
 constexpr size_t kAlign = 256;
-// Keys per attention work-group when the caller leaves it open: large enough to amortise the
-// per-group merge, small enough that the launch has several work-groups per compute unit.
-int default_split_keys(const mkv_config* c, int cap) {
-  const double keys = (double)c->batch * c->n_kv_heads * ((double)c->max_prefill + cap);
-  const double target_groups = 256.0 * 8.0;
-  int ch = 1024;
-  while (ch > 64 && keys / ch < target_groups) ch /= 2;
-  return ch;
-}
+constexpr int kMaxGroups = 4096;          // attention work-groups per launch, at most
+constexpr int kDefaultGroupsPerCU = 3;    // the attention kernel's register budget fits 3 per CU
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -35,8 +28,8 @@ struct Layout {
   // per-layer regions (byte offsets inside a layer block) and the layer stride
   size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
   // scratch regions (absolute offsets), shared by all layers
-  size_t part_o, part_ml, logits, abar, lse, src_map, evict_info, total;
-  int cap, CH, S_max;
+  size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, total;
+  int cap, HL, passes;
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
 };
 
@@ -69,7 +62,8 @@ std::string check_config(const mkv_config* c) {
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return "softmax_scale must be finite and >= 0";
   if (c->score_mode != MKV_SCORE_LAYER_MEAN) return "unknown score_mode";
   if (c->split_keys < 0 || (c->split_keys % 64) != 0) return "split_keys must be a non-negative multiple of 64";
-  if (c->attn_variant < 0 || c->attn_variant > 16) return "attn_variant out of range";
+  if (c->attn_variant < 0 || c->attn_variant > 32) return "attn_variant out of range";
+  if (c->groups_per_cu < 0 || c->groups_per_cu > 16) return "groups_per_cu out of range";
   int64_t cap = c->decode_capacity;
   if (cap == 0) {
     if (c->evict_trigger == MKV_NEVER_EVICT) return "decode_capacity is required with MKV_NEVER_EVICT";
@@ -87,8 +81,8 @@ Layout make_layout(const mkv_config* c) {
   Layout L;
   memset(&L, 0, sizeof L);
   L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + 1;
-  L.CH = c->split_keys ? c->split_keys : default_split_keys(c, L.cap);
-  L.S_max = (c->max_prefill + L.CH - 1) / L.CH + (L.cap + L.CH - 1) / L.CH;
+  L.HL = head_lanes(c->n_q_heads / c->n_kv_heads);
+  L.passes = (c->n_q_heads / c->n_kv_heads + L.HL - 1) / L.HL;
   const size_t es = c->dtype == MKV_BF16 ? 2 : 4;
   const size_t B = c->batch, Hkv = c->n_kv_heads, H = c->n_q_heads, D = c->head_dim;
   size_t o = 0;
@@ -114,8 +108,10 @@ Layout make_layout(const mkv_config* c) {
   L.tpos = take(B * 4);
   L.layer_bytes = o;
   o = L.layer_bytes * (size_t)c->n_layers;
-  L.part_o = take(B * H * L.S_max * D * 4);
-  L.part_ml = take(B * H * L.S_max * 2 * 4);
+  const size_t slots = (size_t)kMaxGroups + B * Hkv * L.passes;
+  L.part_o = take(slots * L.HL * D * 4);
+  L.part_ml = take(slots * L.HL * 2 * 4);
+  L.offs = take((B + 1) * 8);
   L.logits = take(B * H * L.cap * 4);
   L.abar = take(B * L.cap * 4);
   L.lse = take(B * H * 4);
@@ -151,6 +147,7 @@ struct mkv_ctx {
   std::vector<int64_t> h_step;
   std::vector<uint8_t> frozen;
   int last_layer;
+  int target_groups;   // attention work-groups a launch aims for: compute units x groups per unit
   std::string err;
   Profiler prof;
 };
@@ -183,6 +180,7 @@ Scratch scratch_view(const mkv_ctx* c) {
   Scratch s;
   s.part_o = (float*)(c->arena + c->lay.part_o);
   s.part_ml = (float*)(c->arena + c->lay.part_ml);
+  s.offs = (long long*)(c->arena + c->lay.offs);
   s.logits = (float*)(c->arena + c->lay.logits);
   s.abar = (float*)(c->arena + c->lay.abar);
   s.lse = (float*)(c->arena + c->lay.lse);
@@ -282,7 +280,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   Shape& s = c->shape;
   s.B = cfg->batch; s.H = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.G = s.H / s.Hkv;
   s.D = cfg->head_dim; s.bf16 = cfg->dtype == MKV_BF16;
-  s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.CH = c->lay.CH; s.S_max = c->lay.S_max;
+  s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.HL = c->lay.HL; s.passes = c->lay.passes; s.max_groups = kMaxGroups;
   s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
   s.variant = cfg->attn_variant;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
@@ -291,6 +289,14 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0);
   c->h_last_n.assign(cfg->batch, 0);
   hipError_t e = configure_kernels();
+  {
+    int dev = 0, cus = 256;
+    if (e == hipSuccess) e = hipGetDevice(&dev);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    const int per_cu = cfg->groups_per_cu ? cfg->groups_per_cu : kDefaultGroupsPerCU;
+    c->target_groups = cus * per_cu;
+    if (c->target_groups > kMaxGroups) c->target_groups = kMaxGroups;
+  }
   // bookkeeping starts at zero: scores, positions, all lengths, the scratch
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
     char* base = c->arena + c->lay.layer_bytes * (size_t)l;
@@ -345,10 +351,10 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!q || !k_new || !v_new || !out) return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must not be NULL");
   const int B = c->cfg.batch;
-  const int CH = c->lay.CH;
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
-  int n_active = 0, grid_splits = 0, max_n1 = 0;
+  int n_active = 0, max_n1 = 0;
+  long long total_keys = 0;  // length of the flattened key axis of this launch
   for (int b = 0; b < B; ++b) {
     if (seq_mask && !seq_mask[b]) continue;
     const size_t i = (size_t)layer * B + b;
@@ -357,8 +363,7 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
     mask.w[b >> 6] |= 1ull << (b & 63);
     ++n_active;
     const int n1 = c->h_nd[i] + 1;
-    const int ns = (c->h_mlen[i] + CH - 1) / CH + (n1 + CH - 1) / CH;
-    if (ns > grid_splits) grid_splits = ns;
+    total_keys += (long long)c->cfg.n_kv_heads * c->lay.passes * (c->h_mlen[i] + n1);
     if (n1 > max_n1) max_n1 = n1;
   }
   if (n_active == 0) return MKV_OK;
@@ -374,10 +379,19 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
     c->prof.evicted[c->prof.used] = 0;
     (void)hipEventRecord(pe[0], c->stream);
   }
-  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, grid_splits, c->stream);
+  // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
+  // the caller fixed the range length
+  auto round64 = [](long long x) { return (x + 63) / 64 * 64; };
+  long long R = c->cfg.split_keys ? c->cfg.split_keys
+                                  : round64((total_keys + c->target_groups - 1) / c->target_groups);
+  const long long r_min = round64((total_keys + kMaxGroups - 1) / kMaxGroups);
+  if (R < r_min) R = r_min;
+  if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
+  const int n_groups = (int)((total_keys + R - 1) / R);
+  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   if (pe) (void)hipEventRecord(pe[1], c->stream);
-  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, c->stream);
+  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "finish launch");
   if (pe) (void)hipEventRecord(pe[2], c->stream);
   for (int b = 0; b < B; ++b) {

@@ -10,6 +10,8 @@
 
 #include <math.h>
 
+#include <type_traits>
+
 namespace mkv {
 namespace {
 
@@ -108,7 +110,7 @@ struct AttnArgs {
   const char* k_new;
   const char* v_new;
   SeqMask mask;
-  int passes;  // head passes per KV head: ceil(G / head lanes)
+  int R;       // keys per work-group: the flattened key axis is cut into equal ranges
 };
 
 // quad_perm controls that exchange lane i with lane i^K inside every group of four lanes
@@ -120,9 +122,42 @@ __device__ __forceinline__ float quad_xor(float x) {
   else return x;
 }
 
-// Work-group (split, kv head x pass, seq): streams keys [j0, jn) of one segment (prefill or
-// decode) of one KV head, for up to HL of its query heads, and leaves an un-normalised partial
-// (reference, sum, sum p*V) per head.
+// Prefix sums of the per-sequence key counts, built by one wave into LDS: offs[b] = number of keys
+// of all units of sequences < b, where a sequence has `units` = Hkv * passes units of
+// L_b = M_b + n_d + 1 keys each (0 for inactive sequences).  Returns nothing; offs has B+1 entries.
+__device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& lv, const SeqMask& mask,
+                                              int units, long long* offs, int lane) {
+  const int per = (s.B + 63) / 64;
+  const int b0 = lane * per;
+  long long sum = 0;
+  for (int i = 0; i < per; ++i) {
+    const int b = b0 + i;
+    if (b < s.B && mask.active(b)) sum += (long long)units * (lv.mlen[b] + lv.nd[b] + 1);
+  }
+  long long incl = sum;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const long long y = __shfl_up(incl, off);
+    if (lane >= off) incl += y;
+  }
+  long long run = incl - sum;
+  for (int i = 0; i < per; ++i) {
+    const int b = b0 + i;
+    if (b < s.B) {
+      offs[b] = run;
+      if (mask.active(b)) run += (long long)units * (lv.mlen[b] + lv.nd[b] + 1);
+    }
+  }
+  if (lane == 63) offs[s.B] = incl;
+}
+
+// Work-group k streams the keys [k*R, (k+1)*R) of the FLATTENED key axis -- sequence by sequence,
+// inside a sequence unit by unit (unit = one KV head x one pass of up to HL of its query heads),
+// inside a unit the prefill pool and then the decode pool -- so every work-group moves the same
+// number of bytes whatever the mix of sequence lengths, and the launch is exactly as many
+// work-groups as the chip holds at once.  For every unit its range touches ("piece") it leaves an
+// un-normalised partial (reference, sum, sum p*V) per head in slot  k + unit index,  which keeps
+// the slots of one unit contiguous.
 //
 // Lane layout.  LPK adjacent lanes share a key; lane c of a group holds the 16-byte vectors
 // c, c+LPK, ... of the row, so one load instruction of a wave reads 64/LPK rows x (LPK*16)
@@ -137,7 +172,7 @@ __device__ __forceinline__ float quad_xor(float x) {
 //     lanes with quad_perm DPP reads (plus one half-row mirror when HL = 8).
 // With HL = 8 the three exchanges are "xor 7" (row_half_mirror), xor 2 and xor 1, which span the
 // eight lanes; head numbers are the lane's coordinates in that basis.
-template <bool BF16, int D, int HL, int LPK, int IT, int WPB, bool PF, bool DIAG = false>
+template <bool BF16, int D, int HL, int LPK, int IT, int WPB, int NBUF, int DIAG = 0>
 __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) {
   constexpr int kWaves = WPB;
   constexpr int kThreads = WPB * 64;
@@ -153,28 +188,43 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   static_assert(LPK % HL == 0 && (LPK == 16 || LPK == 8), "lane group");
 
   const Shape& s = a.s;
-  const int b = blockIdx.z;
-  if (!a.mask.active(b)) return;
-  const int split = blockIdx.x;
-  const int g = blockIdx.y / a.passes;
-  const int pass = blockIdx.y - g * a.passes;
-  const int M = a.lv.mlen[b];
-  const int n0 = a.lv.nd[b];
-  const int n1 = n0 + 1;  // the pool the softmax sees includes the token appended now
-  const int CH = s.CH;
-  const int cp = (M + CH - 1) / CH;
-  const int cd = (n1 + CH - 1) / CH;
-  if (split >= cp + cd) return;
-  const bool dec = split >= cp;
-  const int j0 = (dec ? split - cp : split) * CH;
-  const int jn = min(dec ? n1 : M, j0 + CH);
-  const int jnew = dec ? n0 : -1;
-
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int c = lane % LPK;
   const int kg = lane / LPK;
+  const int units = s.Hkv * s.passes;
+
+  __shared__ long long offs[kMaxBatch + 1];
+  __shared__ float sm_acc[kWaves][HL][D];
+  __shared__ float sm_m[kWaves][HL];
+  __shared__ float sm_l[kWaves][HL];
+  constexpr int WT = 6144 / (HL * TK);   // decode tiles per logit staging window (24 KiB of LDS)
+  constexpr int SK = WT * TK;            // keys per window
+  __shared__ float sm_logit[HL][SK];
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, offs, lane);
+  __syncthreads();
+  if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
+    for (int b = tid; b <= s.B; b += kThreads) {
+      a.sc.offs[b] = offs[b];
+      if (b < s.B && a.mask.active(b)) a.lv.nd_eff[b] = a.lv.nd[b] + 1;
+    }
+  }
+  const long long total = offs[s.B];
+  long long r0 = (long long)blockIdx.x * a.R;
+  const long long r1 = min(total, r0 + a.R);
+  if (r0 >= r1) return;
+
+  // sequence that holds key r0: last b with offs[b] <= r0 (inactive sequences have empty spans)
+  int b;
+  {
+    int lo = 0, hi = s.B;  // invariant: offs[lo] <= r0 < offs[hi]
+    while (hi - lo > 1) {
+      const int mid = (lo + hi) >> 1;
+      if (offs[mid] <= r0) lo = mid; else hi = mid;
+    }
+    b = lo;
+  }
 
   // head owned by this lane, as coordinates in the exchange basis (see above)
   int hm;
@@ -185,134 +235,296 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     hm = c & (HL - 1);
   }
 
-  const size_t head_row = (size_t)b * s.Hkv + g;
-  const size_t pool_rows = dec ? (size_t)s.dstride : (size_t)s.pstride;
-  const char* kbase = (const char*)(dec ? a.lv.Kd : a.lv.Kp) + head_row * pool_rows * ROWB;
-  const char* vbase = (const char*)(dec ? a.lv.Vd : a.lv.Vp) + head_row * pool_rows * ROWB;
-  const char* knew = a.k_new + head_row * ROWB;
-  const char* vnew = a.v_new + head_row * ROWB;
+  while (r0 < r1) {
+    while (offs[b + 1] <= r0) ++b;      // skip to the sequence of r0 (spans of inactive ones are empty)
+    const int M = a.lv.mlen[b];
+    const int n0 = a.lv.nd[b];
+    const int n1 = n0 + 1;              // the pool the softmax sees includes the token appended now
+    const int L = M + n1;
+    const int ul = (int)((r0 - offs[b]) / L);           // unit inside the sequence
+    const int g = ul / s.passes;
+    const int pass = ul - g * s.passes;
+    const int ka = (int)(r0 - offs[b] - (long long)ul * L);   // first key of the piece in the unit
+    const int ke = (int)min((long long)L, ka + (r1 - r0));     // one past its last key
+    // the piece as two sub-ranges: prefill keys [p0, p1), decode slots [d0, d1)
+    const int p0 = min(ka, M), p1 = min(ke, M);
+    const int d0 = max(ka, M) - M, d1 = max(ke, M) - M;
+    const int ntp = (p1 - p0 + TK - 1) / TK;
+    const int ntd = (d1 - d0 + TK - 1) / TK;
+    const int ntile = ntp + ntd;
+    const int jnew = n0;
 
-  if (split == 0 && blockIdx.y == 0 && tid == 0) a.lv.nd_eff[b] = n1;
+    const size_t head_row = (size_t)b * s.Hkv + g;
+    const char* kpre = (const char*)a.lv.Kp + head_row * (size_t)s.pstride * ROWB;
+    const char* vpre = (const char*)a.lv.Vp + head_row * (size_t)s.pstride * ROWB;
+    const char* kdec = (const char*)a.lv.Kd + head_row * (size_t)s.dstride * ROWB;
+    const char* vdec = (const char*)a.lv.Vd + head_row * (size_t)s.dstride * ROWB;
+    const char* knew = a.k_new + head_row * ROWB;
+    const char* vnew = a.v_new + head_row * ROWB;
 
-  // Append (Alg. 1: pool_d <- pool_d U {(K_t, V_t)}): the work-group whose range holds the new
-  // slot stores the row for later steps; in this step every reader takes it from k_new / v_new.
-  if (dec && pass == 0 && jnew >= j0 && jnew < jn && tid < 2 * NV) {
-    const int vsel = tid / NV, vec = tid - vsel * NV;
-    const char* src = (vsel ? vnew : knew) + vec * 16;
-    char* dst = (char*)(vsel ? a.lv.Vd : a.lv.Kd) + (head_row * pool_rows + (size_t)jnew) * ROWB + vec * 16;
-    *reinterpret_cast<uint4*>(dst) = ldg16(src);
-  }
-
-  // queries in storage form at this lane's vector positions; qv[k] belongs to head hm ^ k
-  uint4 qv[HL][VPL];
-#pragma unroll
-  for (int k = 0; k < HL; ++k) {
-    const int hl = pass * HL + (hm ^ k);
-#pragma unroll
-    for (int vi = 0; vi < VPL; ++vi) {
-      qv[k][vi] = (hl < s.G) ? ldg16(a.q + ((size_t)b * s.H + g * s.G + hl) * ROWB + (vi * LPK + c) * 16)
-                             : make_uint4(0, 0, 0, 0);
+    // Append (Alg. 1: pool_d <- pool_d U {(K_t, V_t)}): the work-group whose piece holds the new
+    // slot stores the row for later steps; in this step every reader takes it from k_new / v_new.
+    if (pass == 0 && jnew >= d0 && jnew < d1 && tid < 2 * NV) {
+      const int vsel = tid / NV, vec = tid - vsel * NV;
+      const char* src = (vsel ? vnew : knew) + vec * 16;
+      char* dst = (char*)(vsel ? a.lv.Vd : a.lv.Kd) + (head_row * (size_t)s.dstride + (size_t)jnew) * ROWB + vec * 16;
+      *reinterpret_cast<uint4*>(dst) = ldg16(src);
     }
-  }
-  const int h_own = pass * HL + hm;                    // head within the KV group
-  const bool own_valid = h_own < s.G;
-  float* const logit_row = a.sc.logits + ((size_t)b * s.H + g * s.G + (own_valid ? h_own : 0)) * s.cap;
-  const bool stash = dec && own_valid && c < HL;       // first owner lane of each head writes
 
-  float m_own = -INFINITY, l_own = 0.f;
-  float acc[HL][VPL][EPV];                             // acc[k] belongs to head hm ^ k
+    // queries in storage form at this lane's vector positions; qv[k] belongs to head hm ^ k
+    uint4 qv[HL][VPL];
 #pragma unroll
-  for (int k = 0; k < HL; ++k)
-#pragma unroll
-    for (int vi = 0; vi < VPL; ++vi)
-#pragma unroll
-      for (int e = 0; e < EPV; ++e) acc[k][vi][e] = 0.f;
-
-  const int ntile = (jn - j0 + TK - 1) / TK;
-
-  auto load_tile = [&](int tt, uint4 (&kr)[IT][VPL], uint4 (&vr)[IT][VPL]) {
-    const int jb = j0 + tt * TK;
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-      const int j = min(jb + it * KPW + kg, jn - 1);  // clamp: masked later
-      const bool isnew = (j == jnew);
-      const char* kp = isnew ? knew : kbase + (size_t)j * ROWB;
-      const char* vp = isnew ? vnew : vbase + (size_t)j * ROWB;
+    for (int k = 0; k < HL; ++k) {
+      const int hl = pass * HL + (hm ^ k);
 #pragma unroll
       for (int vi = 0; vi < VPL; ++vi) {
-        kr[it][vi] = ldg16(kp + (vi * LPK + c) * 16);
-        vr[it][vi] = ldg16(vp + (vi * LPK + c) * 16);
+        qv[k][vi] = (hl < s.G) ? ldg16(a.q + ((size_t)b * s.H + g * s.G + hl) * ROWB + (vi * LPK + c) * 16)
+                               : make_uint4(0, 0, 0, 0);
       }
     }
-  };
+    float* const logit_base = a.sc.logits + ((size_t)b * s.H + g * s.G + pass * HL) * s.cap;
+    const int heads_here = min(HL, s.G - pass * HL);     // real heads of this pass
 
-  // One tile: logits of IT keys per lane group, softmax update by the owner lanes, value
-  // accumulation.  Each owner lane keeps its own running reference m_own, raised only when a
-  // tile's maximum exceeds it by more than kSlack (base-2 units): exp2(s - m) then stays below
-  // 2^kSlack, far from overflow, and the rescale is rare.  Lane groups are merged after the loop.
-  constexpr float kSlack = 8.0f;
-  auto compute_tile = [&](int tt, const uint4 (&kr)[IT][VPL], const uint4 (&vr)[IT][VPL]) {
-    if constexpr (DIAG) {  // tuning aid: memory stream only, no attention math (results are garbage)
-      uint32_t x = 0;
+    float m_own = -INFINITY, l_own = 0.f;
+    float acc[HL][VPL][EPV];                             // acc[k] belongs to head hm ^ k
 #pragma unroll
-      for (int it = 0; it < IT; ++it)
+    for (int k = 0; k < HL; ++k)
 #pragma unroll
-        for (int vi = 0; vi < VPL; ++vi)
-          x ^= kr[it][vi].x ^ kr[it][vi].y ^ kr[it][vi].z ^ kr[it][vi].w ^ vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w;
-      l_own += as_f(x & 0x3f800000u);
-      return;
+      for (int vi = 0; vi < VPL; ++vi)
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[k][vi][e] = 0.f;
+
+    auto load_tile = [&](int tt, uint4 (&kr)[IT][VPL], uint4 (&vr)[IT][VPL]) __attribute__((always_inline)) {
+      const bool dec = tt >= ntp;
+      const int jb = dec ? d0 + (tt - ntp) * TK : p0 + tt * TK;
+      const int jl = (dec ? d1 : p1) - 1;
+      const char* kbase = dec ? kdec : kpre;
+      const char* vbase = dec ? vdec : vpre;
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int j = min(jb + it * KPW + kg, jl);  // clamp: masked later
+        const bool isnew = dec && (j == jnew);
+        const char* kp = isnew ? knew : kbase + (size_t)j * ROWB;
+        const char* vp = isnew ? vnew : vbase + (size_t)j * ROWB;
+#pragma unroll
+        for (int vi = 0; vi < VPL; ++vi) {
+          kr[it][vi] = ldg16(kp + (vi * LPK + c) * 16);
+          vr[it][vi] = ldg16(vp + (vi * LPK + c) * 16);
+        }
+      }
+    };
+
+    // Logits of decode keys are staged in LDS, a window of SK keys at a time, and written out by
+    // the whole work-group when the window (or the piece) ends.  Stores are kept out of the
+    // streaming loop because loads and stores share one completion counter on this hardware: with
+    // a store in the loop, every wait for a tile's loads would also wait for the prefetched tiles,
+    // and waiting for a store's completion under full read load costs microseconds.
+    int win = 0;   // current decode window of the piece
+
+    // One tile: logits of IT keys per lane group, softmax update by the owner lanes, value
+    // accumulation.  Each owner lane keeps its own running reference m_own, raised only when a
+    // tile's maximum exceeds it by more than kSlack (base-2 units): exp2(s - m) then stays below
+    // 2^kSlack, far from overflow, and the rescale is rare.  Lane groups are merged after the loop.
+    constexpr float kSlack = 8.0f;
+    auto compute_tile = [&](int tt, const uint4 (&kr)[IT][VPL], const uint4 (&vr)[IT][VPL]) __attribute__((always_inline)) {
+      if constexpr (DIAG == 1) {  // tuning aid: memory stream only, no attention math (results are garbage)
+        uint32_t x = 0;
+#pragma unroll
+        for (int it = 0; it < IT; ++it)
+#pragma unroll
+          for (int vi = 0; vi < VPL; ++vi)
+            x ^= kr[it][vi].x ^ kr[it][vi].y ^ kr[it][vi].z ^ kr[it][vi].w ^ vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w;
+        l_own += as_f(x & 0x3f800000u);
+        return;
+      }
+      const bool dec = tt >= ntp;
+      const int jb = dec ? d0 + (tt - ntp) * TK : p0 + tt * TK;
+      const int jn = dec ? d1 : p1;
+      float sc[IT];
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        const int j = jb + it * KPW + kg;
+        float x[HL];
+#pragma unroll
+        for (int k = 0; k < HL; ++k) {
+          float d = 0.f;
+          if constexpr (DIAG == 3) d = as_f(kr[it][0].x & 0x3f800000u);  // tuning aid: no QK math
+          else {
+#pragma unroll
+          for (int vi = 0; vi < VPL; ++vi) d = dot_vec<BF16>(kr[it][vi], qv[k][vi], d);
+          }
+          x[k] = d;
+        }
+        // reduce-scatter over the HL lanes that own the heads ...
+        if constexpr (HL == 8) {
+#pragma unroll
+          for (int k = 0; k < 4; ++k) x[k] += dpp_mov<kDppHalfMirror>(x[k ^ 4]);
+        }
+        if constexpr (HL >= 4) {
+#pragma unroll
+          for (int k = 0; k < 2; ++k) x[k] += quad_xor<2>(x[k ^ 2]);
+        }
+        if constexpr (HL >= 2) x[0] += quad_xor<1>(x[1]);
+        // ... then over the LPK/HL lane sets of the key group (same owner position in each)
+        float d = x[0];
+        if constexpr (LPK == 16) {
+          if constexpr (HL <= 1) d += dpp_mov<kDppRowRor + 1>(d);
+          if constexpr (HL <= 2) d += dpp_mov<kDppRowRor + 2>(d);
+          if constexpr (HL <= 4) d += dpp_mov<kDppRowRor + 4>(d);
+          d += dpp_mov<kDppRowRor + 8>(d);
+        } else {  // 8 lanes per key: two keys share a 16-lane row, so rotations would mix keys
+          if constexpr (HL <= 1) d += quad_xor<1>(d);
+          if constexpr (HL <= 2) d += quad_xor<2>(d);
+          if constexpr (HL <= 4) d += __shfl_xor(d, 4);
+        }
+        d *= s.scale_log2;
+        sc[it] = (j < jn) ? d : -INFINITY;
+        if constexpr (DIAG != 4 && DIAG != 6) {
+          // first owner lane of each head stages the logit; slot = key offset inside the window
+          if (dec && c < HL) sm_logit[hm][(tt - ntp - win * WT) * TK + it * KPW + kg] = d;
+        }
+      }
+      float tm = sc[0];
+#pragma unroll
+      for (int it = 1; it < IT; ++it) tm = fmaxf(tm, sc[it]);
+      const bool up = tm > m_own + kSlack;   // also true for the first finite score (m = -inf)
+      if ((DIAG == 5 || DIAG == 6) ? true : (bool)__any(up)) {
+        const float mn = up ? tm : m_own;
+        const float cf = up ? fast_exp2(m_own - mn) : 1.0f;   // exp2(-inf) = 0 on the first raise
+        float cf_o = 0.f;
+        if constexpr (HL == 8) cf_o = dpp_mov<kDppHalfMirror>(cf);
+        l_own *= cf;
+        m_own = mn;
+        // per-head factors, fetched from the owner lanes
+        float cfs[HL];
+        cfs[0] = cf;
+        if constexpr (HL >= 2) cfs[1] = quad_xor<1>(cf);
+        if constexpr (HL >= 4) { cfs[2] = quad_xor<2>(cf); cfs[3] = quad_xor<3>(cf); }
+        if constexpr (HL == 8) {
+          cfs[4] = cf_o; cfs[5] = quad_xor<1>(cf_o); cfs[6] = quad_xor<2>(cf_o); cfs[7] = quad_xor<3>(cf_o);
+        }
+#pragma unroll
+        for (int k = 0; k < HL; ++k)
+#pragma unroll
+          for (int vi = 0; vi < VPL; ++vi)
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[k][vi][e] *= cfs[k];
+      }
+#pragma unroll
+      for (int it = 0; it < IT; ++it) {
+        // a lane set that has seen no key yet has m = -inf and only masked scores: guard exp2(nan)
+        const float p = (sc[it] == -INFINITY) ? 0.f : fast_exp2(sc[it] - m_own);
+        l_own += p;
+        float ps[HL];
+        ps[0] = p;
+        if constexpr (HL >= 2) ps[1] = quad_xor<1>(p);
+        if constexpr (HL >= 4) { ps[2] = quad_xor<2>(p); ps[3] = quad_xor<3>(p); }
+        if constexpr (HL == 8) {
+          const float po = dpp_mov<kDppHalfMirror>(p);
+          ps[4] = po; ps[5] = quad_xor<1>(po); ps[6] = quad_xor<2>(po); ps[7] = quad_xor<3>(po);
+        }
+        if constexpr (DIAG == 2) {  // tuning aid: no p*V math
+#pragma unroll
+          for (int vi = 0; vi < VPL; ++vi) acc[0][vi][0] += ps[HL - 1] * as_f(vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w);
+        } else {
+#pragma unroll
+        for (int k = 0; k < HL; ++k)
+#pragma unroll
+          for (int vi = 0; vi < VPL; ++vi) axpy_vec<BF16>(ps[k], vr[it][vi], acc[k][vi]);
+        }
+      }
+    };
+
+    // NBUF register buffers per wave: the loads of the next NBUF-1 tiles are in flight while a
+    // tile is being worked on (NBUF = 1: load, then compute).  The steady-state loop is unrolled
+    // by NBUF so that every buffer index is a compile-time constant, and inside it the prefetch is
+    // unconditional: a prefetch under an `if` would make the compiler wait for ALL outstanding
+    // loads before every tile (it must assume the branch was not taken), which defeats it.
+    auto run_tiles = [&](int t_lo, int t_hi) __attribute__((always_inline)) {
+      uint4 kbuf[NBUF][IT][VPL], vbuf[NBUF][IT][VPL];
+      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no earlier store is pending inside the loop
+      int tt = t_lo + wave;
+      if constexpr (NBUF == 1) {
+        for (; tt < t_hi; tt += kWaves) {
+          load_tile(tt, kbuf[0], vbuf[0]);
+          compute_tile(tt, kbuf[0], vbuf[0]);
+        }
+      } else {
+        constexpr int AHEAD = (NBUF - 1) * kWaves;
+#pragma unroll
+        for (int u = 0; u < NBUF - 1; ++u)
+          if (tt + u * kWaves < t_hi) load_tile(tt + u * kWaves, kbuf[u], vbuf[u]);
+        // tiles still buffered when the steady state ends, starting at buffer U
+        auto drain = [&](auto U) __attribute__((always_inline)) {
+#pragma unroll
+          for (int i = 0; i < NBUF - 1; ++i) {
+            if (tt < t_hi) {
+              compute_tile(tt, kbuf[(decltype(U)::value + i) % NBUF], vbuf[(decltype(U)::value + i) % NBUF]);
+              tt += kWaves;
+            }
+          }
+        };
+        int left_at = -1;
+        while (left_at < 0) {
+#pragma unroll
+          for (int u = 0; u < NBUF; ++u) {
+            if (tt + AHEAD >= t_hi) { left_at = u; break; }
+            load_tile(tt + AHEAD, kbuf[(u + NBUF - 1) % NBUF], vbuf[(u + NBUF - 1) % NBUF]);
+            compute_tile(tt, kbuf[u], vbuf[u]);
+            tt += kWaves;
+          }
+        }
+        if (left_at == 0) drain(std::integral_constant<int, 0>{});
+        if constexpr (NBUF >= 2) { if (left_at == 1) drain(std::integral_constant<int, 1>{}); }
+        if constexpr (NBUF >= 3) { if (left_at == 2) drain(std::integral_constant<int, 2>{}); }
+        if constexpr (NBUF >= 4) { if (left_at == 3) drain(std::integral_constant<int, 3>{}); }
+        static_assert(NBUF <= 4, "drain cases");
+      }
+    };
+
+    // phases: all prefill tiles plus the first decode window, then one decode window per phase
+    for (int t_lo = 0; t_lo < ntile; ++win) {
+      const int t_hi = min(ntile, ntp + (win + 1) * WT);
+      run_tiles(t_lo, t_hi);
+      const int wk0 = win * SK;                       // window start, in keys after d0
+      const int nk = min(d1 - d0 - wk0, SK);          // staged keys (<= 0: no decode key yet)
+      if constexpr (DIAG != 4 && DIAG != 6) {
+        if (nk > 0) {
+          __syncthreads();
+          for (int h = 0; h < heads_here; ++h)
+            for (int key = tid; key < nk; key += kThreads)
+              if (DIAG != 7 || s.cap < 0) logit_base[(size_t)h * s.cap + d0 + wk0 + key] = sm_logit[h][key];
+          if (t_hi < ntile) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0) before the window is reused
+            __syncthreads();
+          }
+        }
+      }
+      t_lo = t_hi;
     }
-    const int jb = j0 + tt * TK;
-    float sc[IT];
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-      const int j = jb + it * KPW + kg;
-      float x[HL];
-#pragma unroll
-      for (int k = 0; k < HL; ++k) {
-        float d = 0.f;
-#pragma unroll
-        for (int vi = 0; vi < VPL; ++vi) d = dot_vec<BF16>(kr[it][vi], qv[k][vi], d);
-        x[k] = d;
-      }
-      // reduce-scatter over the HL lanes that own the heads ...
-      if constexpr (HL == 8) {
-#pragma unroll
-        for (int k = 0; k < 4; ++k) x[k] += dpp_mov<kDppHalfMirror>(x[k ^ 4]);
-      }
-      if constexpr (HL >= 4) {
-#pragma unroll
-        for (int k = 0; k < 2; ++k) x[k] += quad_xor<2>(x[k ^ 2]);
-      }
-      if constexpr (HL >= 2) x[0] += quad_xor<1>(x[1]);
-      // ... then over the LPK/HL lane sets of the key group (same owner position in each)
-      float d = x[0];
+
+    // merge the lane sets of the wave: common reference per head, then sums across key groups
+    {
+      float mw = m_own;
       if constexpr (LPK == 16) {
-        if constexpr (HL <= 1) d += dpp_mov<kDppRowRor + 1>(d);
-        if constexpr (HL <= 2) d += dpp_mov<kDppRowRor + 2>(d);
-        if constexpr (HL <= 4) d += dpp_mov<kDppRowRor + 4>(d);
-        d += dpp_mov<kDppRowRor + 8>(d);
-      } else {  // 8 lanes per key: two keys share a 16-lane row, so rotations would mix keys
-        if constexpr (HL <= 1) d += quad_xor<1>(d);
-        if constexpr (HL <= 2) d += quad_xor<2>(d);
-        if constexpr (HL <= 4) d += __shfl_xor(d, 4);
+        if constexpr (HL <= 1) mw = fmaxf(mw, dpp_mov<kDppRowRor + 1>(mw));
+        if constexpr (HL <= 2) mw = fmaxf(mw, dpp_mov<kDppRowRor + 2>(mw));
+        if constexpr (HL <= 4) mw = fmaxf(mw, dpp_mov<kDppRowRor + 4>(mw));
+        mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
+      } else {
+        if constexpr (HL <= 1) mw = fmaxf(mw, quad_xor<1>(mw));
+        if constexpr (HL <= 2) mw = fmaxf(mw, quad_xor<2>(mw));
+        if constexpr (HL <= 4) mw = fmaxf(mw, __shfl_xor(mw, 4));
+        mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
       }
-      d *= s.scale_log2;
-      sc[it] = (j < jn) ? d : -INFINITY;
-      if (stash && j < jn) logit_row[j] = d;
-    }
-    float tm = sc[0];
-#pragma unroll
-    for (int it = 1; it < IT; ++it) tm = fmaxf(tm, sc[it]);
-    const bool up = tm > m_own + kSlack;   // also true for the first finite score (m = -inf)
-    if (__any(up)) {
-      const float mn = up ? tm : m_own;
-      const float cf = up ? fast_exp2(m_own - mn) : 1.0f;   // exp2(-inf) = 0 on the first raise
+      mw = fmaxf(mw, __shfl_xor(mw, 16));
+      mw = fmaxf(mw, __shfl_xor(mw, 32));
+      // the owner sets of a head inside one key group saw the same keys and hold identical copies
+      // of m_own and l_own: only the key groups differ.  Scale to the wave's reference and add up
+      // the key groups.
+      const float cf = (m_own == -INFINITY) ? 0.f : fast_exp2(m_own - mw);
       float cf_o = 0.f;
       if constexpr (HL == 8) cf_o = dpp_mov<kDppHalfMirror>(cf);
-      l_own *= cf;
-      m_own = mn;
-      // per-head factors, fetched from the owner lanes
       float cfs[HL];
       cfs[0] = cf;
       if constexpr (HL >= 2) cfs[1] = quad_xor<1>(cf);
@@ -320,130 +532,52 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
       if constexpr (HL == 8) {
         cfs[4] = cf_o; cfs[5] = quad_xor<1>(cf_o); cfs[6] = quad_xor<2>(cf_o); cfs[7] = quad_xor<3>(cf_o);
       }
+      l_own = across_groups_sum<LPK>(l_own * cf);
+      m_own = mw;
 #pragma unroll
       for (int k = 0; k < HL; ++k)
 #pragma unroll
         for (int vi = 0; vi < VPL; ++vi)
 #pragma unroll
-          for (int e = 0; e < EPV; ++e) acc[k][vi][e] *= cfs[k];
+          for (int e = 0; e < EPV; ++e) acc[k][vi][e] = across_groups_sum<LPK>(acc[k][vi][e] * cfs[k]);
     }
-#pragma unroll
-    for (int it = 0; it < IT; ++it) {
-      // a lane set that has seen no key yet has m = -inf and only masked scores: guard exp2(nan)
-      const float p = (sc[it] == -INFINITY) ? 0.f : fast_exp2(sc[it] - m_own);
-      l_own += p;
-      float ps[HL];
-      ps[0] = p;
-      if constexpr (HL >= 2) ps[1] = quad_xor<1>(p);
-      if constexpr (HL >= 4) { ps[2] = quad_xor<2>(p); ps[3] = quad_xor<3>(p); }
-      if constexpr (HL == 8) {
-        const float po = dpp_mov<kDppHalfMirror>(p);
-        ps[4] = po; ps[5] = quad_xor<1>(po); ps[6] = quad_xor<2>(po); ps[7] = quad_xor<3>(po);
-      }
+
+    // wave partial -> LDS -> work-group partial of this piece
+    if (kg == 0) {
 #pragma unroll
       for (int k = 0; k < HL; ++k)
 #pragma unroll
-        for (int vi = 0; vi < VPL; ++vi) axpy_vec<BF16>(ps[k], vr[it][vi], acc[k][vi]);
-    }
-  };
-
-  if constexpr (PF) {
-    // two register buffers, loop unrolled by two so that the prefetch needs no register copies
-    uint4 ka[IT][VPL], va[IT][VPL], kb[IT][VPL], vb[IT][VPL];
-    if (wave < ntile) load_tile(wave, ka, va);
-    for (int tt = wave; tt < ntile; tt += 2 * kWaves) {
-      if (tt + kWaves < ntile) load_tile(tt + kWaves, kb, vb);
-      compute_tile(tt, ka, va);
-      if (tt + kWaves >= ntile) break;
-      if (tt + 2 * kWaves < ntile) load_tile(tt + 2 * kWaves, ka, va);
-      compute_tile(tt + kWaves, kb, vb);
-    }
-  } else {
-    // no software prefetch: the other waves of the SIMD cover the load latency
-    for (int tt = wave; tt < ntile; tt += kWaves) {
-      uint4 ka[IT][VPL], va[IT][VPL];
-      load_tile(tt, ka, va);
-      compute_tile(tt, ka, va);
-    }
-  }
-
-  // merge the lane sets of the wave: common reference per head, then sums across key groups
-  // (and across the LPK/HL owner sets inside a key group for the running sum)
-  {
-    float mw = m_own;
-    if constexpr (LPK == 16) {
-      if constexpr (HL <= 1) mw = fmaxf(mw, dpp_mov<kDppRowRor + 1>(mw));
-      if constexpr (HL <= 2) mw = fmaxf(mw, dpp_mov<kDppRowRor + 2>(mw));
-      if constexpr (HL <= 4) mw = fmaxf(mw, dpp_mov<kDppRowRor + 4>(mw));
-      mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
-    } else {
-      if constexpr (HL <= 1) mw = fmaxf(mw, quad_xor<1>(mw));
-      if constexpr (HL <= 2) mw = fmaxf(mw, quad_xor<2>(mw));
-      if constexpr (HL <= 4) mw = fmaxf(mw, __shfl_xor(mw, 4));
-      mw = fmaxf(mw, dpp_mov<kDppRowRor + 8>(mw));
-    }
-    mw = fmaxf(mw, __shfl_xor(mw, 16));
-    mw = fmaxf(mw, __shfl_xor(mw, 32));
-    // every owner set of a head saw the same keys, so their m_own and l_own are identical copies:
-    // only the key groups differ.  Scale to the wave's reference and add up the key groups.
-    const float cf = (m_own == -INFINITY) ? 0.f : fast_exp2(m_own - mw);
-    float cf_o = 0.f;
-    if constexpr (HL == 8) cf_o = dpp_mov<kDppHalfMirror>(cf);
-    float cfs[HL];
-    cfs[0] = cf;
-    if constexpr (HL >= 2) cfs[1] = quad_xor<1>(cf);
-    if constexpr (HL >= 4) { cfs[2] = quad_xor<2>(cf); cfs[3] = quad_xor<3>(cf); }
-    if constexpr (HL == 8) {
-      cfs[4] = cf_o; cfs[5] = quad_xor<1>(cf_o); cfs[6] = quad_xor<2>(cf_o); cfs[7] = quad_xor<3>(cf_o);
-    }
-    l_own = across_groups_sum<LPK>(l_own * cf);
-    m_own = mw;
+        for (int vi = 0; vi < VPL; ++vi)
 #pragma unroll
-    for (int k = 0; k < HL; ++k)
-#pragma unroll
-      for (int vi = 0; vi < VPL; ++vi)
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) acc[k][vi][e] = across_groups_sum<LPK>(acc[k][vi][e] * cfs[k]);
-  }
-
-  // wave partial -> LDS -> work-group partial
-  __shared__ float sm_acc[kWaves][HL][D];
-  __shared__ float sm_m[kWaves][HL];
-  __shared__ float sm_l[kWaves][HL];
-  if (kg == 0) {
-#pragma unroll
-    for (int k = 0; k < HL; ++k)
-#pragma unroll
-      for (int vi = 0; vi < VPL; ++vi)
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) sm_acc[wave][hm ^ k][(vi * LPK + c) * EPV + e] = acc[k][vi][e];
-    if (c < HL) {
-      sm_m[wave][hm] = m_own;
-      sm_l[wave][hm] = l_own;
+          for (int e = 0; e < EPV; ++e) sm_acc[wave][hm ^ k][(vi * LPK + c) * EPV + e] = acc[k][vi][e];
+      if (c < HL) {
+        sm_m[wave][hm] = m_own;
+        sm_l[wave][hm] = l_own;
+      }
     }
-  }
-  __syncthreads();
-
-  for (int idx = tid; idx < HL * D; idx += kThreads) {
-    const int h = idx / D, d = idx - h * D;
-    const int hl = pass * HL + h;
-    if (hl >= s.G) continue;
-    float mx = sm_m[0][h];
+    __syncthreads();
+    const size_t slot = (size_t)blockIdx.x + (size_t)b * units + ul;
+    for (int idx = tid; idx < HL * D; idx += kThreads) {
+      const int h = idx / D, d = idx - h * D;
+      float mx = sm_m[0][h];
 #pragma unroll
-    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][h]);
-    float o = 0.f, lt = 0.f;
+      for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sm_m[w][h]);
+      float o = 0.f, lt = 0.f;
 #pragma unroll
-    for (int w = 0; w < kWaves; ++w) {
-      const float wgt = fast_exp2(sm_m[w][h] - mx);  // a wave without tiles has reference -inf -> 0
-      o = fmaf(wgt, sm_acc[w][h][d], o);
-      lt = fmaf(wgt, sm_l[w][h], lt);
+      for (int w = 0; w < kWaves; ++w) {
+        // a wave without tiles has reference -inf; if no wave had a tile, mx is -inf as well
+        const float wgt = (sm_m[w][h] == -INFINITY) ? 0.f : fast_exp2(sm_m[w][h] - mx);
+        o = fmaf(wgt, sm_acc[w][h][d], o);
+        lt = fmaf(wgt, sm_l[w][h], lt);
+      }
+      a.sc.part_o[(slot * HL + h) * D + d] = o;
+      if (d == 0) {
+        a.sc.part_ml[(slot * HL + h) * 2] = mx;
+        a.sc.part_ml[(slot * HL + h) * 2 + 1] = lt;
+      }
     }
-    const size_t slot = ((size_t)b * s.H + (g * s.G + hl)) * s.S_max + split;
-    a.sc.part_o[slot * D + d] = o;
-    if (d == 0) {
-      a.sc.part_ml[slot * 2] = mx;
-      a.sc.part_ml[slot * 2 + 1] = lt;
-    }
+    __syncthreads();  // the LDS staging is reused by the next piece
+    r0 += ke - ka;
   }
 }
 
@@ -460,14 +594,11 @@ struct FinishArgs {
   void* out;
   SeqMask mask;
   float inv_H;
+  int R;  // keys per attention work-group of the launch being finished
 };
 
 constexpr int kFinishThreads = 256;
 
-// grid (H + ceil(max n_d / 256), B).  Blocks x < H merge the split partials of head x and write
-// Att_t (Eq. 2).  The other blocks own 256 decode slots each: they rebuild every head's softmax
-// normaliser from the split (max, sum) pairs, turn the stashed logits into probabilities, take the
-// head mean (Eq. 4) and apply I <- alpha*I + abar (Eq. 5), with I = 0 for the new slot (Eq. 6).
 __device__ __forceinline__ float wave_max(float x) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
@@ -479,17 +610,39 @@ __device__ __forceinline__ float wave_sum(float x) {
   return x;
 }
 
-// Softmax normaliser of one head from its split (reference, sum) pairs, by one whole wave:
-// returns the common reference mx and the total sum L relative to it (both base 2).
-__device__ __forceinline__ void wave_merge_ml(const float* ml, int ns, int lane, float& mx, float& L) {
+// Where the attention kernel left the partials of query head h of sequence b: first slot, number
+// of slots, and the head's position inside a slot.
+struct PieceSpan { size_t slot0; int ns; int hs; };
+__device__ __forceinline__ PieceSpan piece_span(const Shape& s, const long long* offs, int R, int b, int h, int L) {
+  const int g = h / s.G, hl = h - g * s.G;
+  const int pass = hl / s.HL;
+  const int ul = g * s.passes + pass;
+  const long long off_u = offs[b] + (long long)ul * L;
+  const long long kf = off_u / R, kl = (off_u + L - 1) / R;
+  PieceSpan p;
+  p.slot0 = (size_t)kf + (size_t)b * s.Hkv * s.passes + ul;
+  p.ns = (int)(kl - kf) + 1;
+  p.hs = hl - pass * s.HL;
+  return p;
+}
+
+// Softmax normaliser of one head from its per-piece (reference, sum) pairs, by one whole wave:
+// returns the common reference mx and the total sum L relative to it (both base 2).  `ml` points
+// at the head's pair in the first slot; consecutive slots are `stride` floats apart.
+__device__ __forceinline__ void wave_merge_ml(const float* ml, int stride, int ns, int lane, float& mx, float& L) {
   float m_loc = -INFINITY;
-  for (int i = lane; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[2 * i]);
+  for (int i = lane; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[(size_t)i * stride]);
   mx = wave_max(m_loc);
   float l_loc = 0.f;
-  for (int i = lane; i < ns; i += 64) l_loc = fmaf(fast_exp2(ml[2 * i] - mx), ml[2 * i + 1], l_loc);
+  for (int i = lane; i < ns; i += 64)
+    l_loc = fmaf(fast_exp2(ml[(size_t)i * stride] - mx), ml[(size_t)i * stride + 1], l_loc);
   L = wave_sum(l_loc);
 }
 
+// grid (H + ceil(max n_d / 256), B).  Blocks x < H merge the partials of head x and write Att_t
+// (Eq. 2).  The other blocks own 256 decode slots each: they rebuild every head's softmax
+// normaliser from the (reference, sum) pairs, turn the stashed logits into probabilities, take the
+// head mean (Eq. 4) and apply I <- alpha*I + abar (Eq. 5), with I = 0 for the new slot (Eq. 6).
 template <int D>
 __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs a) {
   const Shape& s = a.s;
@@ -498,28 +651,31 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   const int M = a.lv.mlen[b];
   const int n1 = a.lv.nd_eff[b];
   const int n0 = n1 - 1;
-  const int ns = (M + s.CH - 1) / s.CH + (n1 + s.CH - 1) / s.CH;
+  const int Lb = M + n1;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  extern __shared__ float smem[];  // head blocks: [S_max] split weights; slot blocks: [H] normalisers
+  const int mlstride = s.HL * 2;
+  extern __shared__ float smem[];  // head blocks: piece weights; slot blocks: [H] normalisers
 
   if ((int)blockIdx.x < s.H) {
     const int h = blockIdx.x;
-    constexpr int SUB = kFinishThreads / D;  // split subsets summed in parallel
+    constexpr int SUB = kFinishThreads / D;  // piece subsets summed in parallel
     const int d = tid % D, sub = tid / D;
-    const size_t slot0 = ((size_t)b * s.H + h) * s.S_max;
-    const float* ml = a.sc.part_ml + slot0 * 2;
+    const PieceSpan sp = piece_span(s, a.sc.offs, a.R, b, h, Lb);
+    const int ns = sp.ns;
+    const float* ml = a.sc.part_ml + (sp.slot0 * s.HL + sp.hs) * 2;
     float mx, L;
-    wave_merge_ml(ml, ns, lane, mx, L);        // every wave computes the same pair
-    for (int i = tid; i < ns; i += kFinishThreads) smem[i] = fast_exp2(ml[2 * i] - mx);
+    wave_merge_ml(ml, mlstride, ns, lane, mx, L);   // every wave computes the same pair
+    for (int i = tid; i < ns; i += kFinishThreads) smem[i] = fast_exp2(ml[(size_t)i * mlstride] - mx);
     __syncthreads();
     float o0 = 0.f, o1 = 0.f;
-    const float* po = a.sc.part_o + slot0 * D + d;
+    const float* po = a.sc.part_o + (sp.slot0 * s.HL + sp.hs) * D + d;
+    const size_t ostride = (size_t)s.HL * D;
     int i = sub;
     for (; i + SUB < ns; i += 2 * SUB) {       // two independent loads in flight
-      o0 = fmaf(smem[i], po[(size_t)i * D], o0);
-      o1 = fmaf(smem[i + SUB], po[(size_t)(i + SUB) * D], o1);
+      o0 = fmaf(smem[i], po[(size_t)i * ostride], o0);
+      o1 = fmaf(smem[i + SUB], po[(size_t)(i + SUB) * ostride], o1);
     }
-    if (i < ns) o0 = fmaf(smem[i], po[(size_t)i * D], o0);
+    if (i < ns) o0 = fmaf(smem[i], po[(size_t)i * ostride], o0);
     __shared__ float red[kFinishThreads];
     red[tid] = o0 + o1;
     __syncthreads();
@@ -541,22 +697,56 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
 
   const int jb = ((int)blockIdx.x - s.H) * kFinishThreads;
   if (jb >= n1) return;
-  for (int h = wave; h < s.H; h += kFinishThreads / 64) {
-    float mx, L;
-    wave_merge_ml(a.sc.part_ml + ((size_t)b * s.H + h) * s.S_max * 2, ns, lane, mx, L);
-    if (lane == 0) smem[h] = mx + log2f(L);
+  // Normalisers of all H heads, with the threads spread over (head, piece subset) so that the
+  // (reference, sum) pairs of every head are fetched in one round of loads: `parts` threads per
+  // head, partial maxima and sums combined through LDS.  smem: [H] normalisers, then 2 x [parts][hc].
+  {
+    const int hc = min(s.H, kFinishThreads);              // heads per round
+    const int parts = kFinishThreads / hc;
+    float* red = smem + s.H;
+    for (int h0 = 0; h0 < s.H; h0 += hc) {
+      const int hh = tid % hc, part = tid / hc;
+      const int h = h0 + hh;
+      const bool on = part < parts && h < s.H;
+      PieceSpan sp = {0, 0, 0};
+      const float* ml = a.sc.part_ml;
+      float m_loc = -INFINITY;
+      if (on) {
+        sp = piece_span(s, a.sc.offs, a.R, b, h, Lb);
+        ml = a.sc.part_ml + (sp.slot0 * s.HL + sp.hs) * 2;
+        for (int i = part; i < sp.ns; i += parts) m_loc = fmaxf(m_loc, ml[(size_t)i * mlstride]);
+        red[part * hc + hh] = m_loc;
+      }
+      __syncthreads();
+      float mx = -INFINITY, l_loc = 0.f;
+      if (on) {
+        for (int p = 0; p < parts; ++p) mx = fmaxf(mx, red[p * hc + hh]);
+        for (int i = part; i < sp.ns; i += parts)
+          l_loc = fmaf(fast_exp2(ml[(size_t)i * mlstride] - mx), ml[(size_t)i * mlstride + 1], l_loc);
+      }
+      __syncthreads();
+      if (on) red[part * hc + hh] = l_loc;
+      __syncthreads();
+      if (on && part == 0) {
+        float L = 0.f;
+        for (int p = 0; p < parts; ++p) L += red[p * hc + hh];
+        smem[h] = mx + log2f(L);
+      }
+      __syncthreads();
+    }
   }
-  __syncthreads();
   const int j = jb + tid;
   if (j >= n1) return;
   float sum0 = 0.f, sum1 = 0.f;
   const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
   int h = 0;
-  for (; h + 1 < s.H; h += 2) {
-    sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
-    sum1 += fast_exp2(lg[(size_t)(h + 1) * s.cap] - smem[h + 1]);
+  for (; h + 3 < s.H; h += 4) {   // four independent loads in flight
+    const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
+    const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
+    sum0 += fast_exp2(x0 - smem[h]) + fast_exp2(x2 - smem[h + 2]);
+    sum1 += fast_exp2(x1 - smem[h + 1]) + fast_exp2(x3 - smem[h + 3]);
   }
-  if (h < s.H) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
+  for (; h < s.H; ++h) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
   const float abar = (sum0 + sum1) * a.inv_H;
   const size_t si = (size_t)b * s.cap + j;
   const float prev = (j == n0) ? 0.f : a.lv.score[si];
@@ -569,11 +759,11 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   }
 }
 
-template <bool BF16, int D, int HL, int IT, int WPB, bool PF, bool DIAG = false>
+template <bool BF16, int D, int HL, int IT, int WPB, int NBUF, int DIAG = 0>
 hipError_t launch_attn_v(const AttnArgs& a, dim3 grid, hipStream_t st) {
   constexpr int NV = D * (BF16 ? 2 : 4) / 16;
   constexpr int LPK = NV < 16 ? NV : 16;
-  hipLaunchKernelGGL((attn_split_kernel<BF16, D, HL, LPK, IT, WPB, PF, DIAG>), grid, dim3(WPB * 64), 0, st, a);
+  hipLaunchKernelGGL((attn_split_kernel<BF16, D, HL, LPK, IT, WPB, NBUF, DIAG>), grid, dim3(WPB * 64), 0, st, a);
   return hipGetLastError();
 }
 
@@ -583,32 +773,36 @@ template <bool BF16, int D, int HL>
 hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
   if constexpr (BF16 && D == 128 && (HL == 4 || HL == 8)) {
     switch (a.s.variant) {
-      case 1: return launch_attn_v<BF16, D, HL, 4, 4, true>(a, grid, st);
-      case 2: return launch_attn_v<BF16, D, HL, 2, 4, true>(a, grid, st);
-      case 3: return launch_attn_v<BF16, D, HL, 4, 4, false>(a, grid, st);
-      case 4: return launch_attn_v<BF16, D, HL, 2, 4, false>(a, grid, st);
-      case 5: return launch_attn_v<BF16, D, HL, 8, 4, false>(a, grid, st);
-      case 6: return launch_attn_v<BF16, D, HL, 8, 4, true>(a, grid, st);
-      case 7: return launch_attn_v<BF16, D, HL, 4, 8, true>(a, grid, st);
-      case 8: return launch_attn_v<BF16, D, HL, 2, 8, true>(a, grid, st);
-      case 9: return launch_attn_v<BF16, D, HL, 4, 2, true>(a, grid, st);
-      case 10: return launch_attn_v<BF16, D, HL, 4, 4, true, true>(a, grid, st);
-      case 11: return launch_attn_v<BF16, D, HL, 4, 4, false, true>(a, grid, st);
-      case 12: return launch_attn_v<BF16, D, HL, 8, 4, false, true>(a, grid, st);
+      case 1: return launch_attn_v<BF16, D, HL, 4, 4, 2>(a, grid, st);
+      case 2: return launch_attn_v<BF16, D, HL, 2, 4, 2>(a, grid, st);
+      case 3: return launch_attn_v<BF16, D, HL, 4, 4, 1>(a, grid, st);
+      case 4: return launch_attn_v<BF16, D, HL, 4, 4, 3>(a, grid, st);
+      case 5: return launch_attn_v<BF16, D, HL, 2, 4, 3>(a, grid, st);
+      case 6: return launch_attn_v<BF16, D, HL, 2, 4, 4>(a, grid, st);
+      case 7: return launch_attn_v<BF16, D, HL, 8, 4, 2>(a, grid, st);
+      case 8: return launch_attn_v<BF16, D, HL, 2, 8, 2>(a, grid, st);
+      case 9: return launch_attn_v<BF16, D, HL, 2, 8, 3>(a, grid, st);
+      case 10: return launch_attn_v<BF16, D, HL, 4, 4, 2, 1>(a, grid, st);
+      case 15: return launch_attn_v<BF16, D, HL, 4, 4, 2, 2>(a, grid, st);
+      case 16: return launch_attn_v<BF16, D, HL, 4, 4, 2, 3>(a, grid, st);
+      case 17: return launch_attn_v<BF16, D, HL, 4, 4, 2, 4>(a, grid, st);
+      case 18: return launch_attn_v<BF16, D, HL, 4, 4, 2, 5>(a, grid, st);
+      case 19: return launch_attn_v<BF16, D, HL, 4, 4, 2, 6>(a, grid, st);
+      case 20: return launch_attn_v<BF16, D, HL, 4, 4, 2, 7>(a, grid, st);
+      case 11: return launch_attn_v<BF16, D, HL, 1, 4, 4>(a, grid, st);
+      case 12: return launch_attn_v<BF16, D, HL, 2, 2, 4>(a, grid, st);
+      case 13: return launch_attn_v<BF16, D, HL, 4, 2, 3>(a, grid, st);
+      case 14: return launch_attn_v<BF16, D, HL, 4, 8, 2>(a, grid, st);
       default: break;
     }
   }
-  return launch_attn_v<BF16, D, HL, 4, 4, true>(a, grid, st);
+  return launch_attn_v<BF16, D, HL, 4, 4, 2>(a, grid, st);
 }
 
 template <bool BF16, int D>
-hipError_t launch_attn_d(const AttnArgs& a0, hipStream_t st, int grid_splits) {
-  AttnArgs a = a0;
-  const int G = a.s.G;
-  const int hl = (G == 1) ? 1 : (G == 2) ? 2 : (G <= 4) ? 4 : 8;  // head lanes per key group
-  a.passes = (G + hl - 1) / hl;
-  dim3 grid(grid_splits, a.s.Hkv * a.passes, a.s.B);
-  switch (hl) {
+hipError_t launch_attn_d(const AttnArgs& a, hipStream_t st, int n_groups) {
+  dim3 grid(n_groups);
+  switch (a.s.HL) {
     case 1: return launch_attn_t<BF16, D, 1>(a, grid, st);
     case 2: return launch_attn_t<BF16, D, 2>(a, grid, st);
     case 4: return launch_attn_t<BF16, D, 4>(a, grid, st);
@@ -619,22 +813,24 @@ hipError_t launch_attn_d(const AttnArgs& a0, hipStream_t st, int grid_splits) {
 }  // namespace
 
 hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, const void* q,
-                       const void* k_new, const void* v_new, const SeqMask& mask, int grid_splits,
-                       hipStream_t st) {
+                       const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
+                       int n_groups, hipStream_t st) {
   AttnArgs a;
   a.s = s; a.lv = lv; a.sc = sc;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
-  a.mask = mask; a.passes = 1;
-  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, st, grid_splits) : launch_attn_d<true, 64>(a, st, grid_splits);
-  return s.D == 128 ? launch_attn_d<false, 128>(a, st, grid_splits) : launch_attn_d<false, 64>(a, st, grid_splits);
+  a.mask = mask; a.R = keys_per_group;
+  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, st, n_groups) : launch_attn_d<true, 64>(a, st, n_groups);
+  return s.D == 128 ? launch_attn_d<false, 128>(a, st, n_groups) : launch_attn_d<false, 64>(a, st, n_groups);
 }
 
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
-                         const SeqMask& mask, int max_nd_eff, hipStream_t st) {
+                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st) {
   FinishArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.inv_H = 1.0f / (float)s.H;
+  a.R = keys_per_group;
   dim3 grid(s.H + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
-  const size_t smem = (size_t)(s.H > s.S_max ? s.H : s.S_max) * sizeof(float);
+  // head blocks: one weight per piece; slot blocks: H normalisers + a 256-entry reduction area
+  const size_t smem = (size_t)(s.H + kFinishThreads > s.max_groups ? s.H + kFinishThreads : s.max_groups) * sizeof(float);
   if (s.D == 128) hipLaunchKernelGGL((finish_kernel<128>), grid, dim3(kFinishThreads), smem, st, a);
   else hipLaunchKernelGGL((finish_kernel<64>), grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();

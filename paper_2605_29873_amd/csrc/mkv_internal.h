@@ -23,8 +23,9 @@ struct Shape {
   int cap;           // row capacity of the decode pool per (seq, kv head)
   int pstride;       // rows between consecutive (seq, kv head) regions of the prefill pool
   int dstride;       // same for the decode pool (>= cap; padded, see the arena layout)
-  int CH;            // keys per attention work-group (split size)
-  int S_max;         // split slots per sequence in the partial buffers
+  int HL;            // query heads one attention pass serves per KV head: 1, 2, 4 or 8
+  int passes;        // passes per KV head: ceil(G / HL)
+  int max_groups;    // most attention work-groups a launch may use (sizes the partial buffers)
   int budget, window;
   int variant;       // attention kernel variant (tuning), 0 = default
   float alpha;
@@ -45,8 +46,9 @@ struct LayerView {
 
 // Per-step scratch, shared by all layers (layers run one after another on one stream).
 struct Scratch {
-  float* part_o;      // [B][H][S_max][D]  un-normalised partial outputs per split
-  float* part_ml;     // [B][H][S_max][2]  (running max, running sum) per split, base-2 units
+  float* part_o;      // [max_groups + B*Hkv*passes][HL][D]  un-normalised partial outputs per piece
+  float* part_ml;     // [max_groups + B*Hkv*passes][HL][2]  (reference, sum) per piece, base-2 units
+  long long* offs;    // [B+1]  prefix sums of the per-sequence key counts of the last launch
   float* logits;      // [B][H][cap]       base-2 logits of decode keys
   float* abar;        // [B][cap]          head-mean decode-slice attention of the last step
   float* lse;         // [B][H]            base-2 log of the softmax normaliser of the last step
@@ -58,16 +60,18 @@ hipError_t launch_ingest(const Shape& s, void* Kpool, void* Vpool, int rows_cap,
                          const void* k, const void* v, int n_tokens, hipStream_t st);
 
 hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, const void* q,
-                       const void* k_new, const void* v_new, const SeqMask& mask, int grid_splits,
-                       hipStream_t st);
+                       const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
+                       int n_groups, hipStream_t st);
 
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
-                         const SeqMask& mask, int max_nd_eff, hipStream_t st);
+                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st);
 
 // Evicts every masked sequence whose pool size exceeds `threshold` back to s.budget.
 hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
                         int threshold, hipStream_t st);
 
 hipError_t configure_kernels();
+
+inline int head_lanes(int G) { return G == 1 ? 1 : G == 2 ? 2 : G <= 4 ? 4 : 8; }
 
 }  // namespace mkv
