@@ -20,7 +20,6 @@ namespace {
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxGroups = 4096;          // attention work-groups per launch, at most
-constexpr int kDefaultGroupsPerCU = 3;    // the attention kernel's register budget fits 3 per CU
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -29,7 +28,7 @@ struct Layout {
   size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, total;
-  int cap, HL, passes;
+  int cap, HL, passes, max_groups;
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
 };
 
@@ -108,7 +107,10 @@ Layout make_layout(const mkv_config* c) {
   L.tpos = take(B * 4);
   L.layer_bytes = o;
   o = L.layer_bytes * (size_t)c->n_layers;
-  const size_t slots = (size_t)kMaxGroups + B * Hkv * L.passes;
+  // a work-group takes at least 64 keys, so small pools never need many partial slots
+  const size_t key_cap = B * Hkv * L.passes * ((size_t)c->max_prefill + L.cap);
+  L.max_groups = (int)(key_cap / 64 + 1 < (size_t)kMaxGroups ? key_cap / 64 + 1 : (size_t)kMaxGroups);
+  const size_t slots = (size_t)L.max_groups + B * Hkv * L.passes;
   L.part_o = take(slots * L.HL * D * 4);
   L.part_ml = take(slots * L.HL * 2 * 4);
   L.offs = take((B + 1) * 8);
@@ -280,7 +282,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   Shape& s = c->shape;
   s.B = cfg->batch; s.H = cfg->n_q_heads; s.Hkv = cfg->n_kv_heads; s.G = s.H / s.Hkv;
   s.D = cfg->head_dim; s.bf16 = cfg->dtype == MKV_BF16;
-  s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.HL = c->lay.HL; s.passes = c->lay.passes; s.max_groups = kMaxGroups;
+  s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.HL = c->lay.HL; s.passes = c->lay.passes; s.max_groups = c->lay.max_groups;
   s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
   s.variant = cfg->attn_variant;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
@@ -293,9 +295,12 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
     int dev = 0, cus = 256;
     if (e == hipSuccess) e = hipGetDevice(&dev);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    const int per_cu = cfg->groups_per_cu ? cfg->groups_per_cu : kDefaultGroupsPerCU;
+    // one launch = exactly the work-groups the chip holds at once (registers and LDS decide)
+    int per_cu = cfg->groups_per_cu;
+    if (per_cu == 0 && e == hipSuccess) e = attn_groups_per_cu(c->shape, &per_cu);
+    if (per_cu < 1) per_cu = 1;
     c->target_groups = cus * per_cu;
-    if (c->target_groups > kMaxGroups) c->target_groups = kMaxGroups;
+    if (c->target_groups > c->lay.max_groups) c->target_groups = c->lay.max_groups;
   }
   // bookkeeping starts at zero: scores, positions, all lengths, the scratch
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
@@ -384,7 +389,7 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   auto round64 = [](long long x) { return (x + 63) / 64 * 64; };
   long long R = c->cfg.split_keys ? c->cfg.split_keys
                                   : round64((total_keys + c->target_groups - 1) / c->target_groups);
-  const long long r_min = round64((total_keys + kMaxGroups - 1) / kMaxGroups);
+  const long long r_min = round64((total_keys + c->lay.max_groups - 1) / c->lay.max_groups);
   if (R < r_min) R = r_min;
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);

@@ -9,6 +9,7 @@
 #include "mkv_internal.h"
 
 #include <math.h>
+#include <string.h>
 
 #include <type_traits>
 
@@ -111,6 +112,7 @@ struct AttnArgs {
   const char* v_new;
   SeqMask mask;
   int R;       // keys per work-group: the flattened key axis is cut into equal ranges
+  int* occupancy;  // host pointer, only for the occupancy query
 };
 
 // quad_perm controls that exchange lane i with lane i^K inside every group of four lanes
@@ -759,11 +761,14 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   }
 }
 
+// grid.x == 0 asks how many work-groups of the variant fit on one compute unit (*a.occupancy).
 template <bool BF16, int D, int HL, int IT, int WPB, int NBUF, int DIAG = 0>
 hipError_t launch_attn_v(const AttnArgs& a, dim3 grid, hipStream_t st) {
   constexpr int NV = D * (BF16 ? 2 : 4) / 16;
   constexpr int LPK = NV < 16 ? NV : 16;
-  hipLaunchKernelGGL((attn_split_kernel<BF16, D, HL, LPK, IT, WPB, NBUF, DIAG>), grid, dim3(WPB * 64), 0, st, a);
+  auto kern = attn_split_kernel<BF16, D, HL, LPK, IT, WPB, NBUF, DIAG>;
+  if (grid.x == 0) return hipOccupancyMaxActiveBlocksPerMultiprocessor(a.occupancy, kern, WPB * 64, 0);
+  hipLaunchKernelGGL(kern, grid, dim3(WPB * 64), 0, st, a);
   return hipGetLastError();
 }
 
@@ -789,6 +794,11 @@ hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
       case 18: return launch_attn_v<BF16, D, HL, 4, 4, 2, 5>(a, grid, st);
       case 19: return launch_attn_v<BF16, D, HL, 4, 4, 2, 6>(a, grid, st);
       case 20: return launch_attn_v<BF16, D, HL, 4, 4, 2, 7>(a, grid, st);
+      case 21: return launch_attn_v<BF16, D, HL, 2, 4, 1>(a, grid, st);
+      case 22: return launch_attn_v<BF16, D, HL, 2, 8, 1>(a, grid, st);
+      case 23: return launch_attn_v<BF16, D, HL, 8, 4, 1>(a, grid, st);
+      case 24: return launch_attn_v<BF16, D, HL, 4, 8, 1>(a, grid, st);
+      case 25: return launch_attn_v<BF16, D, HL, 4, 2, 1>(a, grid, st);
       case 11: return launch_attn_v<BF16, D, HL, 1, 4, 4>(a, grid, st);
       case 12: return launch_attn_v<BF16, D, HL, 2, 2, 4>(a, grid, st);
       case 13: return launch_attn_v<BF16, D, HL, 4, 2, 3>(a, grid, st);
@@ -796,7 +806,9 @@ hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
       default: break;
     }
   }
-  return launch_attn_v<BF16, D, HL, 4, 4, 2>(a, grid, st);
+  // default: 4 keys per lane group and tile, 8 waves per work-group, no software prefetch (the
+  // resident waves hide the load latency at least as well, and it keeps the register count down)
+  return launch_attn_v<BF16, D, HL, 4, 8, 1>(a, grid, st);
 }
 
 template <bool BF16, int D>
@@ -818,9 +830,17 @@ hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, c
   AttnArgs a;
   a.s = s; a.lv = lv; a.sc = sc;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
-  a.mask = mask; a.R = keys_per_group;
+  a.mask = mask; a.R = keys_per_group; a.occupancy = nullptr;
   if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, st, n_groups) : launch_attn_d<true, 64>(a, st, n_groups);
   return s.D == 128 ? launch_attn_d<false, 128>(a, st, n_groups) : launch_attn_d<false, 64>(a, st, n_groups);
+}
+
+hipError_t attn_groups_per_cu(const Shape& s, int* out) {
+  AttnArgs a;
+  memset(&a, 0, sizeof a);
+  a.s = s; a.occupancy = out;
+  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, nullptr, 0) : launch_attn_d<true, 64>(a, nullptr, 0);
+  return s.D == 128 ? launch_attn_d<false, 128>(a, nullptr, 0) : launch_attn_d<false, 64>(a, nullptr, 0);
 }
 
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,

@@ -63,6 +63,9 @@ hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, c
                        const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
                        int n_groups, hipStream_t st);
 
+// How many attention work-groups of this shape's kernel variant are resident per compute unit.
+hipError_t attn_groups_per_cu(const Shape& s, int* out);
+
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
                          const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st);
 
