@@ -8,7 +8,7 @@ that are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = microseconds per decode step per layer (lower is better), with
 tokens/s and the whole-step algorithmic GB/s beside it; `roofline` covers the attention kernel,
-timed with HIP events around every launch in a second pass of the same steps; `cpu_baseline` is the
+timed with start/stop HIP events attached to every launch in a second pass of the same steps; `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--attn-variant", type=int, default=0)
     ap.add_argument("--groups-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB elementwise pass (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     return ap.parse_args()
 
@@ -241,6 +243,18 @@ def cpu_baseline(wl, seconds):
                       f"{per_seq_step_us:.0f} us per sequence-step x batch {wl.batch}; numpy fp64"}
 
 
+def measured_traffic(workload_key: str):
+    """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{workload_key}_pmc.txt")
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -255,6 +269,13 @@ def main():
     mkv.load()
     wls = X.workloads()
     wl = wls[args.workload]
+    if args.calibrate_copy:   # a plain elementwise pass of known size: 1 GiB read + 1 GiB written
+        src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        torch.mul(src, 2.0, out=dst)      # shows up as one elementwise kernel of 2^28 elements
+        torch.cuda.synchronize()
+        del src, dst
     main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant, args.groups_per_cu)
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
@@ -286,10 +307,11 @@ def main():
         "hbm_frac_whole_step": main_res["step_frac_of_hbm_peak"],
         "roofline": {"bound": "hbm", "kernel": "attn_split_kernel",
                      "achieved": main_res["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": main_res["attn_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": main_res["attn_GBps"] / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload),
+                     "traffic_source": f"profiles/{args.workload}_pmc.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, bytes per launch)",
                      "algorithmic_bytes_per_launch": main_res["attn_algorithmic_bytes_per_launch"],
                      "avg_launch_us": main_res["attn_kernel_us"],
-                     "timing": "HIP events around every launch, second pass of the same steps"},
+                     "timing": "start/stop HIP events attached to every launch, second pass of the same steps"},
         "detail": main_res,
         "others": others,
     }

@@ -155,10 +155,11 @@ int mkv_get_lens(mkv_ctx* ctx, int layer, int seq, int* n_prefill, int* n_decode
 
 /* ---- measurement helper (off by default) ---------------------------------------------------- */
 
-/* enable != 0: every following mkv_decode_step brackets its attention kernel, its finishing
- * kernel and its eviction kernels with HIP events on the context's stream (this slows the step a
- * little: use a separate pass for whole-step timing).  enable == 0 stops recording.  Either way
- * the accumulated figures are reset. */
+/* enable != 0: every following mkv_decode_step launches its attention kernel, its finishing
+ * kernel and its eviction kernels with start/stop HIP events attached to the launch itself, so the
+ * recorded times are the kernels' own execution times on the context's stream (the events slow
+ * the step a little: use a separate pass for whole-step timing).  enable == 0 stops recording.
+ * Either way the accumulated figures are reset. */
 int mkv_set_profiling(mkv_ctx* ctx, int enable);
 
 /* Waits for the stream and returns the sums since mkv_set_profiling: microseconds spent in the

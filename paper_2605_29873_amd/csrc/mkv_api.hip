@@ -131,7 +131,7 @@ __global__ void set_int_kernel(int32_t* p, int32_t v) { *p = v; }
 struct Profiler {
   static constexpr int kSlots = 512;       // steps recorded before the sums are folded
   bool on = false;
-  std::vector<hipEvent_t> ev;              // 4 events per slot
+  std::vector<hipEvent_t> ev;              // 6 events per slot: start/stop of attention, finish, eviction
   std::vector<uint8_t> evicted;
   int used = 0;
   double us[3] = {0, 0, 0};
@@ -191,17 +191,19 @@ Scratch scratch_view(const mkv_ctx* c) {
   return s;
 }
 
-// Folds the recorded slots into the sums (waits for the last recorded event).
+constexpr int kEvPerSlot = 6;
+
+// Folds the recorded slots into the sums (waits for the stream to drain first).
 hipError_t prof_fold(mkv_ctx* c) {
   Profiler& p = c->prof;
   if (p.used == 0) return hipSuccess;
-  hipError_t e = hipEventSynchronize(p.ev[(size_t)(p.used - 1) * 4 + 3]);
+  hipError_t e = hipStreamSynchronize(c->stream);
   for (int i = 0; i < p.used && e == hipSuccess; ++i) {
-    hipEvent_t* q = &p.ev[(size_t)i * 4];
+    hipEvent_t* q = &p.ev[(size_t)i * kEvPerSlot];
     float ms[3] = {0, 0, 0};
     e = hipEventElapsedTime(&ms[0], q[0], q[1]);
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms[1], q[1], q[2]);
-    if (e == hipSuccess && p.evicted[i]) e = hipEventElapsedTime(&ms[2], q[2], q[3]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms[1], q[2], q[3]);
+    if (e == hipSuccess && p.evicted[i]) e = hipEventElapsedTime(&ms[2], q[4], q[5]);
     for (int k = 0; k < 3; ++k) p.us[k] += 1000.0 * ms[k];
     p.steps += 1;
     p.evict_steps += p.evicted[i];
@@ -222,7 +224,8 @@ int set_device_int(mkv_ctx* c, int32_t* p, int32_t v) {
 
 // Evicts the sequences of `mask` whose mirror length exceeds `threshold`; returns MKV_OK when no
 // sequence qualifies.
-int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* fired = nullptr) {
+int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* fired = nullptr,
+              const KernelTimer* tm = nullptr) {
   const int B = c->cfg.batch;
   bool any = false;
   for (int b = 0; b < B; ++b)
@@ -230,7 +233,7 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* f
         c->h_nd[(size_t)layer * B + b] > c->cfg.decode_budget) any = true;
   if (fired) *fired = any;
   if (!any) return MKV_OK;
-  hipError_t e = launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream);
+  hipError_t e = launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream, tm);
   if (e != hipSuccess) return fail_hip(c, e, "evict launch");
   for (int b = 0; b < B; ++b) {
     int32_t& n = c->h_nd[(size_t)layer * B + b];
@@ -375,14 +378,15 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   LayerView lv = layer_view(c, layer);
   Scratch sc = scratch_view(c);
   hipEvent_t* pe = nullptr;
+  KernelTimer t_attn, t_fin, t_ev;
   if (c->prof.on) {
     if (c->prof.used == Profiler::kSlots) {
       hipError_t pe_err = prof_fold(c);
       if (pe_err != hipSuccess) return fail_hip(c, pe_err, "profile events");
     }
-    pe = &c->prof.ev[(size_t)c->prof.used * 4];
+    pe = &c->prof.ev[(size_t)c->prof.used * kEvPerSlot];
     c->prof.evicted[c->prof.used] = 0;
-    (void)hipEventRecord(pe[0], c->stream);
+    t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
   }
   // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
   // the caller fixed the range length
@@ -393,12 +397,10 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   if (R < r_min) R = r_min;
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
-  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream);
+  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
-  if (pe) (void)hipEventRecord(pe[1], c->stream);
-  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream);
+  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "finish launch");
-  if (pe) (void)hipEventRecord(pe[2], c->stream);
   for (int b = 0; b < B; ++b) {
     if (!mask.active(b)) continue;
     const size_t i = (size_t)layer * B + b;
@@ -411,16 +413,10 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   int rc = MKV_OK;
   if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
     bool fired = false;
-    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired);
-    if (pe && fired) {
-      (void)hipEventRecord(pe[3], c->stream);
-      c->prof.evicted[c->prof.used] = 1;
-    }
+    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr);
+    if (pe && fired) c->prof.evicted[c->prof.used] = 1;
   }
-  if (pe) {
-    if (!c->prof.evicted[c->prof.used]) (void)hipEventRecord(pe[3], c->stream);
-    c->prof.used += 1;
-  }
+  if (pe) c->prof.used += 1;
   return rc;
 }
 
@@ -558,7 +554,7 @@ int mkv_set_profiling(mkv_ctx* c, int enable) {
   hipError_t e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "stream synchronize");
   if (enable && p.ev.empty()) {
-    p.ev.resize((size_t)Profiler::kSlots * 4);
+    p.ev.resize((size_t)Profiler::kSlots * kEvPerSlot);
     p.evicted.assign(Profiler::kSlots, 0);
     for (size_t i = 0; i < p.ev.size(); ++i) {
       e = hipEventCreate(&p.ev[i]);

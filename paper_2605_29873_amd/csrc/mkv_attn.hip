@@ -8,6 +8,8 @@
 // and V with the arithmetic on the vector ALU.
 #include "mkv_internal.h"
 
+#include <hip/hip_ext.h>
+
 #include <math.h>
 #include <string.h>
 
@@ -174,7 +176,7 @@ __device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& l
 //     lanes with quad_perm DPP reads (plus one half-row mirror when HL = 8).
 // With HL = 8 the three exchanges are "xor 7" (row_half_mirror), xor 2 and xor 1, which span the
 // eight lanes; head numbers are the lane's coordinates in that basis.
-template <bool BF16, int D, int HL, int LPK, int IT, int WPB, int NBUF, int DIAG = 0>
+template <bool BF16, int D, int HL, int LPK, int IT, int WPB, int NBUF>
 __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) {
   constexpr int kWaves = WPB;
   constexpr int kThreads = WPB * 64;
@@ -329,16 +331,6 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     // 2^kSlack, far from overflow, and the rescale is rare.  Lane groups are merged after the loop.
     constexpr float kSlack = 8.0f;
     auto compute_tile = [&](int tt, const uint4 (&kr)[IT][VPL], const uint4 (&vr)[IT][VPL]) __attribute__((always_inline)) {
-      if constexpr (DIAG == 1) {  // tuning aid: memory stream only, no attention math (results are garbage)
-        uint32_t x = 0;
-#pragma unroll
-        for (int it = 0; it < IT; ++it)
-#pragma unroll
-          for (int vi = 0; vi < VPL; ++vi)
-            x ^= kr[it][vi].x ^ kr[it][vi].y ^ kr[it][vi].z ^ kr[it][vi].w ^ vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w;
-        l_own += as_f(x & 0x3f800000u);
-        return;
-      }
       const bool dec = tt >= ntp;
       const int jb = dec ? d0 + (tt - ntp) * TK : p0 + tt * TK;
       const int jn = dec ? d1 : p1;
@@ -350,11 +342,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
 #pragma unroll
         for (int k = 0; k < HL; ++k) {
           float d = 0.f;
-          if constexpr (DIAG == 3) d = as_f(kr[it][0].x & 0x3f800000u);  // tuning aid: no QK math
-          else {
 #pragma unroll
           for (int vi = 0; vi < VPL; ++vi) d = dot_vec<BF16>(kr[it][vi], qv[k][vi], d);
-          }
           x[k] = d;
         }
         // reduce-scatter over the HL lanes that own the heads ...
@@ -381,16 +370,14 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
         }
         d *= s.scale_log2;
         sc[it] = (j < jn) ? d : -INFINITY;
-        if constexpr (DIAG != 4 && DIAG != 6) {
-          // first owner lane of each head stages the logit; slot = key offset inside the window
-          if (dec && c < HL) sm_logit[hm][(tt - ntp - win * WT) * TK + it * KPW + kg] = d;
-        }
+        // first owner lane of each head stages the logit; slot = key offset inside the window
+        if (dec && c < HL) sm_logit[hm][(tt - ntp - win * WT) * TK + it * KPW + kg] = d;
       }
       float tm = sc[0];
 #pragma unroll
       for (int it = 1; it < IT; ++it) tm = fmaxf(tm, sc[it]);
       const bool up = tm > m_own + kSlack;   // also true for the first finite score (m = -inf)
-      if ((DIAG == 5 || DIAG == 6) ? true : (bool)__any(up)) {
+      if (__any(up)) {
         const float mn = up ? tm : m_own;
         const float cf = up ? fast_exp2(m_own - mn) : 1.0f;   // exp2(-inf) = 0 on the first raise
         float cf_o = 0.f;
@@ -425,15 +412,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
           const float po = dpp_mov<kDppHalfMirror>(p);
           ps[4] = po; ps[5] = quad_xor<1>(po); ps[6] = quad_xor<2>(po); ps[7] = quad_xor<3>(po);
         }
-        if constexpr (DIAG == 2) {  // tuning aid: no p*V math
-#pragma unroll
-          for (int vi = 0; vi < VPL; ++vi) acc[0][vi][0] += ps[HL - 1] * as_f(vr[it][vi].x ^ vr[it][vi].y ^ vr[it][vi].z ^ vr[it][vi].w);
-        } else {
 #pragma unroll
         for (int k = 0; k < HL; ++k)
 #pragma unroll
           for (int vi = 0; vi < VPL; ++vi) axpy_vec<BF16>(ps[k], vr[it][vi], acc[k][vi]);
-        }
       }
     };
 
@@ -490,16 +472,14 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
       run_tiles(t_lo, t_hi);
       const int wk0 = win * SK;                       // window start, in keys after d0
       const int nk = min(d1 - d0 - wk0, SK);          // staged keys (<= 0: no decode key yet)
-      if constexpr (DIAG != 4 && DIAG != 6) {
-        if (nk > 0) {
+      if (nk > 0) {
+        __syncthreads();
+        for (int h = 0; h < heads_here; ++h)
+          for (int key = tid; key < nk; key += kThreads)
+            logit_base[(size_t)h * s.cap + d0 + wk0 + key] = sm_logit[h][key];
+        if (t_hi < ntile) {
+          __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0) before the window is reused
           __syncthreads();
-          for (int h = 0; h < heads_here; ++h)
-            for (int key = tid; key < nk; key += kThreads)
-              if (DIAG != 7 || s.cap < 0) logit_base[(size_t)h * s.cap + d0 + wk0 + key] = sm_logit[h][key];
-          if (t_hi < ntile) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0) before the window is reused
-            __syncthreads();
-          }
         }
       }
       t_lo = t_hi;
@@ -742,7 +722,17 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   float sum0 = 0.f, sum1 = 0.f;
   const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
   int h = 0;
-  for (; h + 3 < s.H; h += 4) {   // four independent loads in flight
+  for (; h + 15 < s.H; h += 16) {   // sixteen independent loads in flight
+    float x[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) x[u] = lg[(size_t)(h + u) * s.cap];
+#pragma unroll
+    for (int u = 0; u < 16; u += 2) {
+      sum0 += fast_exp2(x[u] - smem[h + u]);
+      sum1 += fast_exp2(x[u + 1] - smem[h + u + 1]);
+    }
+  }
+  for (; h + 3 < s.H; h += 4) {
     const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
     const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
     sum0 += fast_exp2(x0 - smem[h]) + fast_exp2(x2 - smem[h + 2]);
@@ -762,63 +752,47 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
 }
 
 // grid.x == 0 asks how many work-groups of the variant fit on one compute unit (*a.occupancy).
-template <bool BF16, int D, int HL, int IT, int WPB, int NBUF, int DIAG = 0>
-hipError_t launch_attn_v(const AttnArgs& a, dim3 grid, hipStream_t st) {
+// With `tm`, the launch carries start/stop events that time the kernel alone.
+template <bool BF16, int D, int HL, int IT, int WPB, int NBUF>
+hipError_t launch_attn_v(const AttnArgs& a, dim3 grid, hipStream_t st, const KernelTimer* tm) {
   constexpr int NV = D * (BF16 ? 2 : 4) / 16;
   constexpr int LPK = NV < 16 ? NV : 16;
-  auto kern = attn_split_kernel<BF16, D, HL, LPK, IT, WPB, NBUF, DIAG>;
+  auto kern = attn_split_kernel<BF16, D, HL, LPK, IT, WPB, NBUF>;
   if (grid.x == 0) return hipOccupancyMaxActiveBlocksPerMultiprocessor(a.occupancy, kern, WPB * 64, 0);
-  hipLaunchKernelGGL(kern, grid, dim3(WPB * 64), 0, st, a);
+  if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(WPB * 64), 0, st, tm->start, tm->stop, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(WPB * 64), 0, st, a);
   return hipGetLastError();
 }
 
-// Tile depth, work-group size and prefetch.  Variant 0 is the tuned default; the others exist for
-// tuning runs on the Llama/Qwen-shaped bf16 kernels only.
+// Keys per lane group and tile, waves per work-group, register buffers.  Variant 0 is the tuned
+// default; the others exist for tuning runs on the Llama/Qwen-shaped bf16 kernels (all of them
+// compute the same result).
 template <bool BF16, int D, int HL>
-hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st) {
+hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st, const KernelTimer* tm) {
   if constexpr (BF16 && D == 128 && (HL == 4 || HL == 8)) {
     switch (a.s.variant) {
-      case 1: return launch_attn_v<BF16, D, HL, 4, 4, 2>(a, grid, st);
-      case 2: return launch_attn_v<BF16, D, HL, 2, 4, 2>(a, grid, st);
-      case 3: return launch_attn_v<BF16, D, HL, 4, 4, 1>(a, grid, st);
-      case 4: return launch_attn_v<BF16, D, HL, 4, 4, 3>(a, grid, st);
-      case 5: return launch_attn_v<BF16, D, HL, 2, 4, 3>(a, grid, st);
-      case 6: return launch_attn_v<BF16, D, HL, 2, 4, 4>(a, grid, st);
-      case 7: return launch_attn_v<BF16, D, HL, 8, 4, 2>(a, grid, st);
-      case 8: return launch_attn_v<BF16, D, HL, 2, 8, 2>(a, grid, st);
-      case 9: return launch_attn_v<BF16, D, HL, 2, 8, 3>(a, grid, st);
-      case 10: return launch_attn_v<BF16, D, HL, 4, 4, 2, 1>(a, grid, st);
-      case 15: return launch_attn_v<BF16, D, HL, 4, 4, 2, 2>(a, grid, st);
-      case 16: return launch_attn_v<BF16, D, HL, 4, 4, 2, 3>(a, grid, st);
-      case 17: return launch_attn_v<BF16, D, HL, 4, 4, 2, 4>(a, grid, st);
-      case 18: return launch_attn_v<BF16, D, HL, 4, 4, 2, 5>(a, grid, st);
-      case 19: return launch_attn_v<BF16, D, HL, 4, 4, 2, 6>(a, grid, st);
-      case 20: return launch_attn_v<BF16, D, HL, 4, 4, 2, 7>(a, grid, st);
-      case 21: return launch_attn_v<BF16, D, HL, 2, 4, 1>(a, grid, st);
-      case 22: return launch_attn_v<BF16, D, HL, 2, 8, 1>(a, grid, st);
-      case 23: return launch_attn_v<BF16, D, HL, 8, 4, 1>(a, grid, st);
-      case 24: return launch_attn_v<BF16, D, HL, 4, 8, 1>(a, grid, st);
-      case 25: return launch_attn_v<BF16, D, HL, 4, 2, 1>(a, grid, st);
-      case 11: return launch_attn_v<BF16, D, HL, 1, 4, 4>(a, grid, st);
-      case 12: return launch_attn_v<BF16, D, HL, 2, 2, 4>(a, grid, st);
-      case 13: return launch_attn_v<BF16, D, HL, 4, 2, 3>(a, grid, st);
-      case 14: return launch_attn_v<BF16, D, HL, 4, 8, 2>(a, grid, st);
+      case 1: return launch_attn_v<BF16, D, HL, 4, 4, 1>(a, grid, st, tm);
+      case 2: return launch_attn_v<BF16, D, HL, 4, 4, 2>(a, grid, st, tm);
+      case 3: return launch_attn_v<BF16, D, HL, 2, 4, 2>(a, grid, st, tm);
+      case 4: return launch_attn_v<BF16, D, HL, 2, 8, 1>(a, grid, st, tm);
+      case 5: return launch_attn_v<BF16, D, HL, 4, 8, 2>(a, grid, st, tm);
+      case 6: return launch_attn_v<BF16, D, HL, 8, 4, 1>(a, grid, st, tm);
       default: break;
     }
   }
   // default: 4 keys per lane group and tile, 8 waves per work-group, no software prefetch (the
   // resident waves hide the load latency at least as well, and it keeps the register count down)
-  return launch_attn_v<BF16, D, HL, 4, 8, 1>(a, grid, st);
+  return launch_attn_v<BF16, D, HL, 4, 8, 1>(a, grid, st, tm);
 }
 
 template <bool BF16, int D>
-hipError_t launch_attn_d(const AttnArgs& a, hipStream_t st, int n_groups) {
+hipError_t launch_attn_d(const AttnArgs& a, hipStream_t st, int n_groups, const KernelTimer* tm) {
   dim3 grid(n_groups);
   switch (a.s.HL) {
-    case 1: return launch_attn_t<BF16, D, 1>(a, grid, st);
-    case 2: return launch_attn_t<BF16, D, 2>(a, grid, st);
-    case 4: return launch_attn_t<BF16, D, 4>(a, grid, st);
-    default: return launch_attn_t<BF16, D, 8>(a, grid, st);
+    case 1: return launch_attn_t<BF16, D, 1>(a, grid, st, tm);
+    case 2: return launch_attn_t<BF16, D, 2>(a, grid, st, tm);
+    case 4: return launch_attn_t<BF16, D, 4>(a, grid, st, tm);
+    default: return launch_attn_t<BF16, D, 8>(a, grid, st, tm);
   }
 }
 
@@ -826,33 +800,35 @@ hipError_t launch_attn_d(const AttnArgs& a, hipStream_t st, int n_groups) {
 
 hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, const void* q,
                        const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
-                       int n_groups, hipStream_t st) {
+                       int n_groups, hipStream_t st, const KernelTimer* tm) {
   AttnArgs a;
   a.s = s; a.lv = lv; a.sc = sc;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
   a.mask = mask; a.R = keys_per_group; a.occupancy = nullptr;
-  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, st, n_groups) : launch_attn_d<true, 64>(a, st, n_groups);
-  return s.D == 128 ? launch_attn_d<false, 128>(a, st, n_groups) : launch_attn_d<false, 64>(a, st, n_groups);
+  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, st, n_groups, tm) : launch_attn_d<true, 64>(a, st, n_groups, tm);
+  return s.D == 128 ? launch_attn_d<false, 128>(a, st, n_groups, tm) : launch_attn_d<false, 64>(a, st, n_groups, tm);
 }
 
 hipError_t attn_groups_per_cu(const Shape& s, int* out) {
   AttnArgs a;
   memset(&a, 0, sizeof a);
   a.s = s; a.occupancy = out;
-  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, nullptr, 0) : launch_attn_d<true, 64>(a, nullptr, 0);
-  return s.D == 128 ? launch_attn_d<false, 128>(a, nullptr, 0) : launch_attn_d<false, 64>(a, nullptr, 0);
+  if (s.bf16) return s.D == 128 ? launch_attn_d<true, 128>(a, nullptr, 0, nullptr) : launch_attn_d<true, 64>(a, nullptr, 0, nullptr);
+  return s.D == 128 ? launch_attn_d<false, 128>(a, nullptr, 0, nullptr) : launch_attn_d<false, 64>(a, nullptr, 0, nullptr);
 }
 
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
-                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st) {
+                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
+                         const KernelTimer* tm) {
   FinishArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.inv_H = 1.0f / (float)s.H;
   a.R = keys_per_group;
   dim3 grid(s.H + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
   // head blocks: one weight per piece; slot blocks: H normalisers + a 256-entry reduction area
   const size_t smem = (size_t)(s.H + kFinishThreads > s.max_groups ? s.H + kFinishThreads : s.max_groups) * sizeof(float);
-  if (s.D == 128) hipLaunchKernelGGL((finish_kernel<128>), grid, dim3(kFinishThreads), smem, st, a);
-  else hipLaunchKernelGGL((finish_kernel<64>), grid, dim3(kFinishThreads), smem, st, a);
+  auto kern = s.D == 128 ? finish_kernel<128> : finish_kernel<64>;
+  if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, tm->start, tm->stop, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();
 }
 

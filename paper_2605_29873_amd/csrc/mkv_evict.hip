@@ -3,6 +3,8 @@
 // Also the token-major -> head-major ingest copy used by the prefill pool.
 #include "mkv_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace mkv {
 namespace {
 
@@ -227,16 +229,20 @@ hipError_t configure_kernels() {
 }
 
 hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
-                        int threshold, hipStream_t st) {
+                        int threshold, hipStream_t st, const KernelTimer* tm) {
   EvictArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = threshold;
   const size_t smem = (size_t)s.cap * 8;
-  hipLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, a);
+  // with a timer: start is taken at the selection kernel, stop after the row mover
+  if (tm) hipExtLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, tm->start, nullptr, 0, a);
+  else hipLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rowb = s.D * (s.bf16 ? 2 : 4);
-  hipLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
-                     0, st, a, rowb);
+  if (tm) hipExtLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
+                                0, st, nullptr, tm->stop, 0, a, rowb);
+  else hipLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
+                          0, st, a, rowb);
   return hipGetLastError();
 }
 

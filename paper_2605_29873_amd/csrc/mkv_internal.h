@@ -56,22 +56,26 @@ struct Scratch {
   int32_t* evict_info;  // [B][2]          (first moved slot, new pool size) of the last selection
 };
 
+// Events that bracket one kernel launch (start and stop are recorded by the launch itself).
+struct KernelTimer { hipEvent_t start, stop; };
+
 hipError_t launch_ingest(const Shape& s, void* Kpool, void* Vpool, int rows_cap, int seq, int row0,
                          const void* k, const void* v, int n_tokens, hipStream_t st);
 
 hipError_t launch_attn(const Shape& s, const LayerView& lv, const Scratch& sc, const void* q,
                        const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
-                       int n_groups, hipStream_t st);
+                       int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
 
 // How many attention work-groups of this shape's kernel variant are resident per compute unit.
 hipError_t attn_groups_per_cu(const Shape& s, int* out);
 
 hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc, void* out,
-                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st);
+                         const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
+                         const KernelTimer* tm = nullptr);
 
 // Evicts every masked sequence whose pool size exceeds `threshold` back to s.budget.
 hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
-                        int threshold, hipStream_t st);
+                        int threshold, hipStream_t st, const KernelTimer* tm = nullptr);
 
 hipError_t configure_kernels();
 
