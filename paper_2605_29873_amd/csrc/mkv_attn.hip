@@ -777,6 +777,10 @@ hipError_t launch_attn_t(const AttnArgs& a, dim3 grid, hipStream_t st, const Ker
       case 4: return launch_attn_v<BF16, D, HL, 2, 8, 1>(a, grid, st, tm);
       case 5: return launch_attn_v<BF16, D, HL, 4, 8, 2>(a, grid, st, tm);
       case 6: return launch_attn_v<BF16, D, HL, 8, 4, 1>(a, grid, st, tm);
+      case 7: return launch_attn_v<BF16, D, HL, 2, 8, 3>(a, grid, st, tm);
+      case 8: return launch_attn_v<BF16, D, HL, 2, 8, 4>(a, grid, st, tm);
+      case 9: return launch_attn_v<BF16, D, HL, 2, 8, 2>(a, grid, st, tm);
+      case 10: return launch_attn_v<BF16, D, HL, 1, 8, 4>(a, grid, st, tm);
       default: break;
     }
   }

@@ -90,6 +90,40 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
   if (tid == 0) { sh_prefix = 0u; sh_krem = k_evict; sh_first = n; }
   __syncthreads();
 
+  if (k_evict == 1) {
+    // The paper's own cadence (one token leaves per step once the pool is full): the selection is
+    // an arg-min over (score, slot), one block-wide reduction instead of the radix passes.
+    __shared__ unsigned long long wave_best[kSelWaves];
+    unsigned long long best = ~0ull;
+    for (int j = tid; j < n_cand; j += kSelThreads) {
+      const unsigned long long v = ((unsigned long long)ordered_key(raw[j]) << 32) | (uint32_t)j;
+      best = v < best ? v : best;
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+      const unsigned long long o = __shfl_xor(best, off);
+      best = o < best ? o : best;
+    }
+    if ((tid & 63) == 0) wave_best[tid >> 6] = best;
+    __syncthreads();
+    best = wave_best[0];
+#pragma unroll
+    for (int w = 1; w < kSelWaves; ++w) best = wave_best[w] < best ? wave_best[w] : best;
+    const int e = (int)(uint32_t)best;          // the evicted slot; survivors above it move down by one
+    int32_t* map1 = a.sc.src_map + (size_t)b * s.cap;
+    for (int j = e + 1 + tid; j < n; j += kSelThreads) {
+      map1[j - 1] = j;
+      score[j - 1] = __builtin_bit_cast(float, raw[j]);
+      pos[j - 1] = posl[j];
+    }
+    if (tid == 0) {
+      info[0] = e;
+      info[1] = n - 1;
+      a.lv.nd[b] = n - 1;
+    }
+    return;
+  }
+
   // radix select: after the pass for byte `p`, sh_prefix holds the top bytes of the threshold
   // and sh_krem how many candidates to take among those that match the prefix
   for (int p = 3; p >= 0; --p) {
@@ -162,13 +196,16 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
 }
 
 constexpr int kMoveThreads = 1024;
-constexpr int kMoveUnroll = 4;
-constexpr int kSliceBytes = 64;
+constexpr int kSliceBytes = 128;
 
-// Stable in-place row compaction.  grid (row slices, Hkv * 2, B): a work-group owns a 64-byte
+// Stable in-place row compaction.  grid (row slices, Hkv * 2, B): a work-group owns a 128-byte
 // column strip of one head's K or V pool and walks the destination slots upwards.  Because a
 // survivor only ever moves to a lower slot, reading a round's sources before a barrier and writing
 // after it can never overwrite a row that is still to be read.
+// U rows per thread and round: 8 lets a pool of up to 1024 rows move in a single round (latency
+// matters there: 18 -> 8 us at 512 rows); large pools run better with one-row rounds, which
+// interleave the reads and the writes of different work-groups (55 -> 45 us at 16 x 2048 rows).
+template <int kMoveUnroll>
 __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArgs a, int rowb) {
   const Shape& s = a.s;
   const int b = blockIdx.z;
@@ -239,10 +276,11 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rowb = s.D * (s.bf16 ? 2 : 4);
-  if (tm) hipExtLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
-                                0, st, nullptr, tm->stop, 0, a, rowb);
-  else hipLaunchKernelGGL(evict_move_kernel, dim3(rowb / kSliceBytes, s.Hkv * 2, s.B), dim3(kMoveThreads),
-                          0, st, a, rowb);
+  constexpr int kRowsPerPass = kMoveThreads / (kSliceBytes / 16);
+  auto kern = s.budget <= kRowsPerPass * 8 ? evict_move_kernel<8> : evict_move_kernel<1>;
+  const dim3 grid(rowb / kSliceBytes, s.Hkv * 2, s.B);
+  if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, nullptr, tm->stop, 0, a, rowb);
+  else hipLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, a, rowb);
   return hipGetLastError();
 }
 
