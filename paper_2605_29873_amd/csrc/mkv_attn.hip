@@ -426,14 +426,23 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     // loads before every tile (it must assume the branch was not taken), which defeats it.
     auto run_tiles = [&](int t_lo, int t_hi) __attribute__((always_inline)) {
       uint4 kbuf[NBUF][IT][VPL], vbuf[NBUF][IT][VPL];
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no earlier store is pending inside the loop
       int tt = t_lo + wave;
       if constexpr (NBUF == 1) {
+        // the first tile's loads go out before the wait that clears earlier stores (and the query
+        // loads), so that their latency overlaps with it
+        const bool any = tt < t_hi;
+        if (any) load_tile(tt, kbuf[0], vbuf[0]);
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no earlier store is pending inside the loop
+        if (any) {
+          compute_tile(tt, kbuf[0], vbuf[0]);
+          tt += kWaves;
+        }
         for (; tt < t_hi; tt += kWaves) {
           load_tile(tt, kbuf[0], vbuf[0]);
           compute_tile(tt, kbuf[0], vbuf[0]);
         }
       } else {
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no earlier store is pending inside the loop
         constexpr int AHEAD = (NBUF - 1) * kWaves;
 #pragma unroll
         for (int u = 0; u < NBUF - 1; ++u)

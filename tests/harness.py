@@ -59,7 +59,7 @@ class Lockstep:
     identical scores, and the decision must then match bit for bit."""
 
     def __init__(self, mkv, wl: X.Workload, layer: int = 0, split_keys: int = 0, seqs=None,
-                 active=None):
+                 active=None, n_layers: int | None = None, device_fill_unfollowed: bool = False):
         """seqs: the sequences the oracle follows (default: all); active: the sequences the GPU
         steps (default: seqs).  Sequences that are active but not followed load the GPU at the
         real batch size; they evict through the library's own trigger check."""
@@ -67,7 +67,9 @@ class Lockstep:
         self.seqs = list(range(wl.batch)) if seqs is None else list(seqs)
         self.active = list(self.seqs) if active is None else list(active)
         assert set(self.seqs) <= set(self.active)
-        self.ctx = make_ctx(mkv, wl, manual_evict=True, layers=layer + 1, split_keys=split_keys)
+        self.device_fill = device_fill_unfollowed   # unfollowed sequences: values drawn on the device
+        self.ctx = make_ctx(mkv, wl, manual_evict=True, layers=layer + 1 if n_layers is None else n_layers,
+                            split_keys=split_keys)
         self.oracles = {s: oracle_state(wl) for s in self.seqs}
         self.out = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim),
                                dtype=torch.bfloat16 if wl.dtype == "bf16" else torch.float32,
@@ -83,8 +85,22 @@ class Lockstep:
             self.mkv.mkv_destroy(self.ctx)
             self.ctx = None
 
+    def _device_kv(self, n):
+        """N(0,1) rows drawn on the device in the storage dtype (for sequences nobody follows)."""
+        wl = self.wl
+        dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        shape = (n, wl.n_kv_heads, wl.head_dim)
+        return (torch.randn(shape, device="cuda", dtype=torch.float32).to(dt),
+                torch.randn(shape, device="cuda", dtype=torch.float32).to(dt))
+
     def prefill(self):
         for s in self.active:
+            if self.device_fill and s not in self.oracles:
+                m = X.prefill_len(self.wl, s)
+                dk, dv = self._device_kv(m)
+                self.mkv.mkv_prefill_append(self.ctx, self.layer, s, dk.data_ptr(), dv.data_ptr(), m)
+                torch.cuda.synchronize()
+                continue
             k, v = X.prefill_kv(self.wl, self.layer, s)
             half = k.shape[0] // 2                      # two appends: exercises the row offset
             for lo, hi in ((0, half), (half, k.shape[0])):
@@ -97,6 +113,13 @@ class Lockstep:
 
     def load_snapshot(self, n_d: int, t_now: int):
         for s in self.active:
+            if self.device_fill and s not in self.oracles:
+                dk, dv = self._device_kv(n_d)
+                rng = np.random.default_rng(s)
+                pos = np.sort(rng.choice(t_now, n_d, replace=False)).astype(np.int32)
+                sc = (rng.random(n_d, dtype=np.float32) * 1e-3).astype(np.float32)
+                self.mkv.mkv_load_decode(self.ctx, self.layer, s, dk.data_ptr(), dv.data_ptr(), sc, pos, t_now)
+                continue
             k, v, sc, pos = X.decode_snapshot(self.wl, self.layer, s, n_d, t_now)
             dk, dv = to_device(k, self.wl.dtype), to_device(v, self.wl.dtype)
             self.mkv.mkv_load_decode(self.ctx, self.layer, s, dk.data_ptr(), dv.data_ptr(), sc, pos, t_now)

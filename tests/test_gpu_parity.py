@@ -91,6 +91,20 @@ def test_cfg5_shape_two_layers_sampled(mkv):
     assert ls.evictions == 1
 
 
+def test_cfg5_full_size_one_layer_of_32_sampled(mkv):
+    # the full 86 GB context (32 layers x 32 sequences x (16384 + 4160) tokens) in the bench's
+    # launch configuration; layer 17 is filled and stepped, sequence 9 is followed by the oracle,
+    # the other 31 sequences hold device-drawn values
+    wl = WL["cfg5"]
+    ls = Lockstep(mkv, wl, layer=17, seqs=[9], active=range(wl.batch), n_layers=wl.n_layers,
+                  device_fill_unfollowed=True)
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 1, 30000)
+    _run(ls, 3, t0=30000)
+    assert ls.evictions == 1
+    print(f"cfg5 full: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
 @pytest.mark.parametrize("H,Hkv,D,dtype", [
     (4, 4, 64, "bf16"),      # G = 1
     (4, 2, 128, "f32"),      # G = 2, fp32 rows of 512 bytes
