@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--attn-variant", type=int, default=0)
     ap.add_argument("--groups-per-cu", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--variants", action="store_true",
+                    help="also time score-rule variants of the main workload (same kernels, other parameters)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB elementwise pass (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -243,6 +245,25 @@ def cpu_baseline(wl, seconds):
                       f"{per_seq_step_us:.0f} us per sequence-step x batch {wl.batch}; numpy fp64"}
 
 
+def variant_workloads(wl):
+    """Parameter settings of the same kernels that mimic the comparison systems the paper times in
+    its throughput figure (their cache rules only, not the systems): all at the decode position
+    where the budgeted pools are full and a never-evicting cache holds `steps` tokens."""
+    from paper_2605_29873_amd import inputs as X
+    chunk = wl.evict_trigger - wl.decode_budget + 1
+    full_len = min(wl.steps, 12288)
+    return {
+        "moment-kv (alpha, window as configured)": wl,
+        "moment-kv, paper cadence (evict 1 per step, no window)":
+            X.scaled(wl, evict_trigger=wl.decode_budget, recent_window=0),
+        "cumulative scores + recent window (alpha=1)": X.scaled(wl, alpha=1.0),
+        "instantaneous scores + recent window (alpha=0)": X.scaled(wl, alpha=0.0),
+        "sliding window only (window = budget)": X.scaled(wl, recent_window=wl.decode_budget),
+        f"full cache (no eviction, {full_len} decode tokens held)":
+            X.scaled(wl, decode_budget=full_len, evict_trigger=full_len + 16 * chunk, recent_window=0),
+    }
+
+
 def measured_traffic(workload_key: str):
     """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{workload_key}_pmc.txt")
@@ -315,6 +336,13 @@ def main():
         "detail": main_res,
         "others": others,
     }
+    if args.variants:
+        line["variants"] = {}
+        for name, w in variant_workloads(wl).items():
+            r = measure(w, min(args.steps, 128), 8, args.split_keys, args.attn_variant, args.groups_per_cu)
+            line["variants"][name] = {k: r[k] for k in ("us_per_step_per_layer", "tokens_per_s", "attn_kernel_us",
+                                                         "finish_kernel_us", "evict_us_per_evicting_launch",
+                                                         "evicting_launches", "pool_tokens_per_layer")}
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
     print(json.dumps(line))
