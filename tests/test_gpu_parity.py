@@ -193,3 +193,46 @@ def test_full_cache_run_needs_no_eviction(mkv):
     ls.prefill()
     _run(ls, 120)
     assert ls.evictions == 0
+
+
+def _random_workload(rng, i):
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    D = int(rng.choice([64, 128]))
+    dtype = str(rng.choice(["bf16", "f32"]))
+    budget = int(rng.integers(1, 90))
+    chunk = int(rng.integers(1, 40))
+    W = int(rng.integers(0, budget + 1)) if rng.random() < 0.5 else 0
+    M = int(rng.choice([0, 1, 63, 64, 65, 200, 777]))
+    return X.Workload(f"rand{i}", batch=int(rng.integers(1, 5)), n_layers=1, n_q_heads=G * Hkv, n_kv_heads=Hkv,
+                      head_dim=D, dtype=dtype, prefill_min=M // 2, prefill_max=M, decode_budget=budget,
+                      evict_trigger=budget + chunk - 1, recent_window=W, alpha=float(rng.choice([0.2, 0.8, 0.98])),
+                      steps=0, hh_prob=0.05, seed=1000 + i)
+
+
+@pytest.mark.parametrize("i", range(12))
+def test_random_shapes_lockstep(mkv, i):
+    # seeded sweep over head groupings, dims, dtypes, budgets, chunks, windows and ragged prefills,
+    # with 64-key work-group ranges so that units are cut into many pieces at odd places
+    rng = np.random.default_rng(4242 + i)
+    wl = _random_workload(rng, i)
+    ls = Lockstep(mkv, wl, split_keys=int(rng.choice([0, 64, 128])))
+    ls.prefill()
+    steps = wl.evict_trigger + 2 * (wl.evict_trigger - wl.decode_budget + 1) + 3
+    _run(ls, min(steps, 160), check_abar=True)
+    assert ls.evictions >= 1 or steps > 160
+
+
+@pytest.mark.parametrize("G,n_d", [(7, 1700), (8, 800), (4, 3300), (1, 6500), (2, 3200)])
+def test_decode_pools_longer_than_one_logit_window(mkv, G, n_d):
+    # the attention kernel stages decode logits in LDS windows (768 .. 6144 keys depending on the
+    # head grouping): pools longer than a window, cut at odd places by 64-key and automatic ranges
+    wl = X.Workload("window", batch=2, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=128, dtype="bf16",
+                    prefill_min=100, prefill_max=300, decode_budget=n_d, evict_trigger=n_d + 1,
+                    recent_window=5, alpha=0.9, steps=0, hh_prob=0.02)
+    for split in (0, 64):
+        ls = Lockstep(mkv, wl, split_keys=split)
+        ls.prefill()
+        ls.load_snapshot(n_d - 1, 3 * n_d)
+        _run(ls, 4, t0=3 * n_d, check_abar=True)
+        assert ls.evictions == 2
