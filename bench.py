@@ -38,6 +38,9 @@ def parse_args():
     ap.add_argument("--split-keys", type=int, default=0)
     ap.add_argument("--attn-variant", type=int, default=0)
     ap.add_argument("--groups-per-cu", type=int, default=0)
+    ap.add_argument("--q-len", type=int, default=0,
+                    help="tokens per sequence and call: 0 = mkv_decode_step (the headline path); N >= 1 = "
+                         "mkv_decode_step_multi with N query rows (matrix-core kernel), reported under 'multi_query'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variants", action="store_true",
                     help="also time score-rule variants of the main workload (same kernels, other parameters)")
@@ -59,19 +62,21 @@ class Job:
 
     BANK = 64
 
-    def __init__(self, wl, split_keys=0, variant=0, gpc=0):
+    def __init__(self, wl, split_keys=0, variant=0, gpc=0, q_len=0):
         import torch
         import paper_2605_29873_amd.binding as mkv
         from paper_2605_29873_amd import inputs as X
         self.torch, self.mkv, self.X, self.wl = torch, mkv, X, wl
+        self.q_len = q_len
         self.tdtype = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
         self.lens = [X.prefill_len(wl, s) for s in range(wl.batch)]
         cfg = mkv.make_config(
             n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
             head_dim=wl.head_dim, dtype=mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32,
             max_prefill=wl.prefill_max, decode_budget=wl.decode_budget, evict_trigger=wl.evict_trigger,
-            decode_capacity=wl.capacity, recent_window=wl.recent_window, alpha=wl.alpha,
+            decode_capacity=wl.capacity + max(0, q_len - 1), recent_window=wl.recent_window, alpha=wl.alpha,
             softmax_scale=0.0, score_mode=0, split_keys=split_keys, attn_variant=variant, groups_per_cu=gpc,
+            max_q_len=q_len,
             stream=torch.cuda.current_stream().cuda_stream)
         self.arena_bytes = mkv.mkv_required_bytes(cfg)
         self.ctx = mkv.mkv_create(cfg)
@@ -114,11 +119,15 @@ class Job:
             qs, ks, vs = zip(*(X.step_batch(wl, layer, 4 * wl.capacity + t) for t in range(self.BANK)))
             per_layer.append((to_device(torch, X, np.stack(qs), wl.dtype), to_device(torch, X, np.stack(ks), wl.dtype),
                               to_device(torch, X, np.stack(vs), wl.dtype)))
+        if self.q_len:   # [BANK, B, heads, D] -> [BANK / q_len, B, q_len, heads, D]
+            n = self.q_len
+            per_layer = [tuple(a[:self.BANK // n * n].view(self.BANK // n, n, *a.shape[1:]).transpose(1, 2).contiguous()
+                               for a in trio) for trio in per_layer]
         self.q = [per_layer[l % drawn][0] for l in layers]
         self.k = [per_layer[l % drawn][1] for l in layers]
         self.v = [per_layer[l % drawn][2] for l in layers]
         self.shift = [l // drawn for l in layers]
-        self.out = torch.empty((wl.batch, wl.n_q_heads, wl.head_dim), dtype=self.tdtype, device="cuda")
+        self.out = torch.empty((wl.batch, max(1, self.q_len), wl.n_q_heads, wl.head_dim), dtype=self.tdtype, device="cuda")
         torch.cuda.synchronize()
 
     def close(self):
@@ -130,9 +139,13 @@ def run_steps(job: Job, n: int):
     out_ptr = job.out.data_ptr()
     for _ in range(n):
         for layer in range(wl.n_layers):
-            i = (job.t + job.shift[layer]) % job.BANK
-            mkv.mkv_decode_step(ctx, layer, job.q[layer][i].data_ptr(), job.k[layer][i].data_ptr(),
-                                job.v[layer][i].data_ptr(), out_ptr)
+            i = (job.t + job.shift[layer]) % job.q[layer].shape[0]
+            if job.q_len:
+                mkv.mkv_decode_step_multi(ctx, layer, job.q_len, job.q[layer][i].data_ptr(), job.k[layer][i].data_ptr(),
+                                          job.v[layer][i].data_ptr(), out_ptr)
+            else:
+                mkv.mkv_decode_step(ctx, layer, job.q[layer][i].data_ptr(), job.k[layer][i].data_ptr(),
+                                    job.v[layer][i].data_ptr(), out_ptr)
         job.t += 1
 
 
@@ -147,15 +160,16 @@ def algorithmic_bytes(job: Job, n_d_before: list[int]):
     on the scores and are left out of the numerator, which is therefore conservative."""
     wl = job.wl
     b = wl.itemsize
+    nq = max(1, job.q_len)                                # tokens appended per sequence and call
     row = wl.n_kv_heads * wl.head_dim * b * 2            # K and V bytes of one token of one layer
     attn = 0
     rest = 0
     for m, n0 in zip(job.lens, n_d_before):
-        n1 = n0 + 1
+        n1 = n0 + nq
         attn += (m + n1) * row                            # K, V read once
-        attn += wl.n_q_heads * wl.head_dim * b            # q read
-        attn += row                                       # append write
-        rest += wl.n_q_heads * wl.head_dim * b            # out write
+        attn += nq * wl.n_q_heads * wl.head_dim * b       # q read
+        attn += nq * row                                  # append write
+        rest += nq * wl.n_q_heads * wl.head_dim * b       # out write
         rest += n1 * 4 * 2                                # I read + write
     return attn + rest, attn
 
@@ -173,8 +187,9 @@ def time_region(job: Job, steps: int):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
-def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0):
-    job = Job(wl, split_keys, variant, gpc)
+def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0):
+    job = Job(wl, split_keys, variant, gpc, q_len)
+    nq = max(1, q_len)
     try:
         run_steps(job, warmup)
         # sizes the pools will have over the timed steps (deterministic: +1 per step, back to the
@@ -187,7 +202,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0):
             tb, ab = algorithmic_bytes(job, sim)
             total_bytes += tb
             attn_bytes += ab
-            sim = [n + 1 for n in sim]
+            sim = [n + nq for n in sim]
             if any(n > wl.evict_trigger for n in sim):
                 evict_steps += 1
             sim = [wl.decode_budget if n > wl.evict_trigger else n for n in sim]
@@ -204,7 +219,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0):
             "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
             "ms_per_step": gpu_s * 1e3 / steps,
             "wall_ms_per_step": wall_s * 1e3 / steps,
-            "tokens_per_s": wl.batch * steps / gpu_s,
+            "tokens_per_s": wl.batch * nq * steps / gpu_s,
             "step_algorithmic_GBps": total_bytes * wl.n_layers / gpu_s / 1e9,
             "step_frac_of_hbm_peak": total_bytes * wl.n_layers / gpu_s / 1e9 / HBM_PEAK_GBPS,
             "attn_kernel_us": prof["attn_us"] / n_launch,
@@ -336,6 +351,11 @@ def main():
         "detail": main_res,
         "others": others,
     }
+    if args.q_len:
+        r = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant, args.groups_per_cu, args.q_len)
+        r["q_len"] = args.q_len
+        r["note"] = "one call = q_len tokens per sequence; us_per_step_per_layer is per call"
+        line["multi_query"] = r
     if args.variants:
         line["variants"] = {}
         for name, w in variant_workloads(wl).items():

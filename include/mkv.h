@@ -66,8 +66,9 @@ typedef struct {
   int32_t evict_trigger;   /* T_e >= B_d: mkv_decode_step evicts back to B_d when the decode pool
                               exceeds T_e.  T_e == B_d is the paper (Alg. 1 "if |pool_d| > B_d").
                               MKV_NEVER_EVICT: only mkv_evict evicts                            */
-  int32_t decode_capacity; /* decode slots per sequence; 0 => evict_trigger + 1.  Required (> B_d)
-                              with MKV_NEVER_EVICT.  At most 16384                              */
+  int32_t decode_capacity; /* decode slots per sequence; 0 => evict_trigger + max(1, max_q_len), which
+                              is also the least allowed.  Required (> B_d) with MKV_NEVER_EVICT.
+                              At most 16384                                                     */
   int32_t recent_window;   /* W <= B_d: the W newest decode tokens are never evicted.  0 is the
                               paper ("regardless of position or recency")                       */
   float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
@@ -78,6 +79,9 @@ typedef struct {
   int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default             */
   int32_t groups_per_cu;   /* tuning: attention work-groups per compute unit a launch aims for;
                               0 => library default                                              */
+  int32_t max_q_len;       /* largest q_len mkv_decode_step_multi will be called with (1..16);
+                              0 => that entry point is disabled and takes no memory.  Needs
+                              MKV_BF16 and head_dim 128                                         */
   void*   stream;          /* hipStream_t, borrowed; NULL => the default stream                  */
   void*   arena;           /* optional device pointer, 256-byte aligned, caller-owned, must outlive
                               the context; NULL => the library allocates and frees              */
@@ -115,6 +119,22 @@ int mkv_prefill_append(mkv_ctx* ctx, int layer, int seq, const void* k, const vo
 int mkv_decode_step(mkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
                     void* out, const uint8_t* seq_mask);
 
+/* q_len decode steps of every active sequence in one pass over the cache (chunked or speculative
+ * decoding): the result equals q_len consecutive mkv_decode_step calls whose capacity check is
+ * held back until the last of them.
+ *   q     device pointer [batch, q_len, n_q_heads, head_dim]
+ *   k_new device pointer [batch, q_len, n_kv_heads, head_dim]  appended in order, each with I = 0
+ *   v_new device pointer [batch, q_len, n_kv_heads, head_dim]
+ *   out   device pointer [batch, q_len, n_q_heads, head_dim]   Att of Eq. 2 per query row
+ * Query row i attends to the prefill pool, the decode pool and the appended tokens 0..i (Eq. 2 over
+ * the pool as it stands at that step).  The scores take q_len momentum updates in row order
+ * (Eq. 4, Eq. 5), an appended token starting at I = 0 in its own step (Eq. 6); then every active
+ * sequence whose decode pool exceeds evict_trigger is evicted back to decode_budget (Eq. 7-9).
+ * Needs cfg.max_q_len >= q_len >= 1 (else MKV_ERR_ARG; MKV_ERR_STATE when max_q_len is 0).
+ * MKV_ERR_CAPACITY if an active sequence has fewer than q_len free decode slots. */
+int mkv_decode_step_multi(mkv_ctx* ctx, int layer, int q_len, const void* q, const void* k_new,
+                          const void* v_new, void* out, const uint8_t* seq_mask);
+
 /* Capacity enforcement on demand (Eq. 7-9): every selected sequence whose decode pool exceeds
  * decode_budget loses its overflow lowest-score tokens outside the recent window -- ties go to
  * the older token -- and the survivors' K, V, score and position rows are compacted in order of
@@ -146,6 +166,7 @@ int mkv_read_kv(mkv_ctx* ctx, int layer, int seq, int pool, int kv_head, void* k
 /* After mkv_decode_step(layer): the head-mean decode-slice attention abar (Eq. 4) the step added
  * to the scores, for the pool as it was before that step's eviction (host float[capacity]), and the
  * natural-log softmax normaliser per query head (host float[n_q_heads]).  Either may be NULL.
+ * After mkv_decode_step_multi: the same two for its last query row.
  * MKV_ERR_STATE if `layer` was not the layer stepped last. */
 int mkv_read_probs(mkv_ctx* ctx, int layer, int seq, float* abar, float* lse_per_head,
                    int capacity, int* n_out);

@@ -21,7 +21,7 @@ MKV_ERR_CAPACITY, MKV_ERR_NOMEM, MKV_ERR_HIP = -4, -5, -6
 MKV_NEVER_EVICT = 2**31 - 1
 
 EXPORTS = ["mkv_required_bytes", "mkv_create", "mkv_destroy", "mkv_prefill_append",
-           "mkv_decode_step", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
+           "mkv_decode_step", "mkv_decode_step_multi", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
            "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_get_lens", "mkv_set_profiling",
            "mkv_read_profile", "mkv_last_error"]
 
@@ -33,7 +33,7 @@ class mkv_config(C.Structure):
                 ("evict_trigger", C.c_int32), ("decode_capacity", C.c_int32),
                 ("recent_window", C.c_int32), ("alpha", C.c_float), ("softmax_scale", C.c_float),
                 ("score_mode", C.c_int32), ("split_keys", C.c_int32), ("attn_variant", C.c_int32),
-                ("groups_per_cu", C.c_int32),
+                ("groups_per_cu", C.c_int32), ("max_q_len", C.c_int32),
                 ("stream", C.c_void_p),
                 ("arena", C.c_void_p), ("arena_bytes", C.c_size_t)]
 
@@ -63,6 +63,7 @@ def load() -> C.CDLL:
     lib.mkv_destroy.argtypes = [vp]
     lib.mkv_prefill_append.argtypes = [vp, i32, i32, vp, vp, i32]
     lib.mkv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.mkv_decode_step_multi.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.mkv_evict.argtypes = [vp, i32, i32]
     lib.mkv_read_scores.argtypes = [vp, i32, i32, vp, vp, i32, C.POINTER(i32)]
     lib.mkv_write_scores.argtypes = [vp, i32, i32, vp, i32]
@@ -119,6 +120,14 @@ def mkv_decode_step(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, seq_mask=None) -> 
         seq_mask = np.ascontiguousarray(seq_mask, dtype=np.uint8)
         mp = seq_mask.ctypes.data
     _check(ctx, load().mkv_decode_step(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, mp))
+
+
+def mkv_decode_step_multi(ctx, layer, q_len, q_ptr, k_ptr, v_ptr, out_ptr, seq_mask=None) -> None:
+    mp = None
+    if seq_mask is not None:
+        seq_mask = np.ascontiguousarray(seq_mask, dtype=np.uint8)
+        mp = seq_mask.ctypes.data
+    _check(ctx, load().mkv_decode_step_multi(ctx, layer, q_len, q_ptr, k_ptr, v_ptr, out_ptr, mp))
 
 
 def mkv_evict(ctx, layer, seq=-1) -> None:

@@ -29,6 +29,7 @@ struct Layout {
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, total;
   int cap, HL, passes, max_groups;
+  int mq_passes;          // most passes per KV head of a multi-query step (0: entry point disabled)
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
 };
 
@@ -63,14 +64,18 @@ std::string check_config(const mkv_config* c) {
   if (c->split_keys < 0 || (c->split_keys % 64) != 0) return "split_keys must be a non-negative multiple of 64";
   if (c->attn_variant < 0 || c->attn_variant > 32) return "attn_variant out of range";
   if (c->groups_per_cu < 0 || c->groups_per_cu > 16) return "groups_per_cu out of range";
+  if (c->max_q_len < 0 || c->max_q_len > 16) return "max_q_len must lie in [0, 16]";
+  if (c->max_q_len > 0 && (c->dtype != MKV_BF16 || c->head_dim != 128))
+    return "max_q_len > 0 needs MKV_BF16 and head_dim 128";
+  const int64_t grow = c->max_q_len > 1 ? c->max_q_len : 1;   // most tokens one call appends
   int64_t cap = c->decode_capacity;
   if (cap == 0) {
     if (c->evict_trigger == MKV_NEVER_EVICT) return "decode_capacity is required with MKV_NEVER_EVICT";
-    cap = (int64_t)c->evict_trigger + 1;
+    cap = (int64_t)c->evict_trigger + grow;
   }
   if (cap <= c->decode_budget) return "decode_capacity must exceed decode_budget";
-  if (c->evict_trigger != MKV_NEVER_EVICT && cap < (int64_t)c->evict_trigger + 1)
-    return "decode_capacity must be at least evict_trigger + 1";
+  if (c->evict_trigger != MKV_NEVER_EVICT && cap < (int64_t)c->evict_trigger + grow)
+    return "decode_capacity must be at least evict_trigger + max(1, max_q_len)";
   if (cap > kMaxDecodeCapacity) return fmt("decode capacity %lld above the supported %d", (long long)cap, kMaxDecodeCapacity);
   if (c->arena && ((uintptr_t)c->arena % kAlign) != 0) return "arena must be 256-byte aligned";
   return "";
@@ -79,25 +84,28 @@ std::string check_config(const mkv_config* c) {
 Layout make_layout(const mkv_config* c) {
   Layout L;
   memset(&L, 0, sizeof L);
-  L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + 1;
-  L.HL = head_lanes(c->n_q_heads / c->n_kv_heads);
-  L.passes = (c->n_q_heads / c->n_kv_heads + L.HL - 1) / L.HL;
+  const int grow = c->max_q_len > 1 ? c->max_q_len : 1;
+  const int G = c->n_q_heads / c->n_kv_heads;
+  L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + grow;
+  L.HL = head_lanes(G);
+  L.passes = (G + L.HL - 1) / L.HL;
+  if (c->max_q_len > 0) {
+    const int hp = mq_heads_per_pass(G, c->max_q_len);   // fewest heads per pass = most passes
+    L.mq_passes = (G + hp - 1) / hp;
+  }
   const size_t es = c->dtype == MKV_BF16 ? 2 : 4;
   const size_t B = c->batch, Hkv = c->n_kv_heads, H = c->n_q_heads, D = c->head_dim;
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
-  const char* pad_env = getenv("MKV_PAD_ROWS");
-  const char* skew_env = getenv("MKV_KV_SKEW");
   // each (seq, kv head) region is followed by 4 KiB of padding: with power-of-two region sizes the
   // work-groups that run side by side would otherwise all hit the same memory channels (measured:
   // +10 % attention bandwidth on the ragged 16-sequence Llama layer)
-  const int pad_rows = pad_env ? atoi(pad_env) : (int)(4096 / (D * es));
-  const size_t skew = skew_env ? (size_t)atol(skew_env) : 0;
+  const int pad_rows = (int)(4096 / (D * es));
   L.pstride = c->max_prefill ? c->max_prefill + pad_rows : 0;
   L.dstride = L.cap + pad_rows;
-  L.Kp = take(B * Hkv * (size_t)L.pstride * D * es + skew);
+  L.Kp = take(B * Hkv * (size_t)L.pstride * D * es);
   L.Vp = take(B * Hkv * (size_t)L.pstride * D * es);
-  L.Kd = take(B * Hkv * (size_t)L.dstride * D * es + skew);
+  L.Kd = take(B * Hkv * (size_t)L.dstride * D * es);
   L.Vd = take(B * Hkv * (size_t)L.dstride * D * es);
   L.score = take(B * L.cap * 4);
   L.pos = take(B * L.cap * 4);
@@ -108,15 +116,18 @@ Layout make_layout(const mkv_config* c) {
   L.layer_bytes = o;
   o = L.layer_bytes * (size_t)c->n_layers;
   // a work-group takes at least 64 keys, so small pools never need many partial slots
-  const size_t key_cap = B * Hkv * L.passes * ((size_t)c->max_prefill + L.cap);
+  const size_t most_passes = L.passes > L.mq_passes ? L.passes : L.mq_passes;
+  const size_t key_cap = B * Hkv * most_passes * ((size_t)c->max_prefill + L.cap);
   L.max_groups = (int)(key_cap / 64 + 1 < (size_t)kMaxGroups ? key_cap / 64 + 1 : (size_t)kMaxGroups);
   const size_t slots = (size_t)L.max_groups + B * Hkv * L.passes;
-  L.part_o = take(slots * L.HL * D * 4);
-  L.part_ml = take(slots * L.HL * 2 * 4);
+  const size_t mq_slots = L.mq_passes ? (size_t)L.max_groups + B * Hkv * L.mq_passes : 0;
+  const size_t rows = slots * L.HL > mq_slots * 16 ? slots * L.HL : mq_slots * 16;   // partial rows
+  L.part_o = take(rows * D * 4);
+  L.part_ml = take(rows * 2 * 4);
   L.offs = take((B + 1) * 8);
-  L.logits = take(B * H * L.cap * 4);
+  L.logits = take(B * H * grow * L.cap * 4);
   L.abar = take(B * L.cap * 4);
-  L.lse = take(B * H * 4);
+  L.lse = take(B * H * grow * 4);
   L.src_map = take(B * L.cap * 4);
   L.evict_info = take(B * 2 * 4);
   L.total = o;
@@ -149,7 +160,9 @@ struct mkv_ctx {
   std::vector<int64_t> h_step;
   std::vector<uint8_t> frozen;
   int last_layer;
+  int last_q_len;      // query rows of the step taken last
   int target_groups;   // attention work-groups a launch aims for: compute units x groups per unit
+  int mq_target_groups;  // same for the multi-query kernel
   std::string err;
   Profiler prof;
 };
@@ -242,6 +255,87 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* f
   return MKV_OK;
 }
 
+// One pass of Algorithm 1 over the active sequences of a layer, appending q_len tokens per
+// sequence; `mq` selects the multi-query kernels (q, k_new, v_new and out then carry q_len rows per
+// sequence).
+int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k_new, const void* v_new,
+         void* out, const uint8_t* seq_mask) {
+  if (!c) return MKV_ERR_ARG;
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
+  if (!q || !k_new || !v_new || !out) return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must not be NULL");
+  const int B = c->cfg.batch;
+  const int G = c->cfg.n_q_heads / c->cfg.n_kv_heads;
+  int passes = c->lay.passes;
+  if (mq) {
+    const int hp = mq_heads_per_pass(G, q_len);
+    passes = (G + hp - 1) / hp;
+  }
+  SeqMask mask;
+  memset(&mask, 0, sizeof mask);
+  int n_active = 0, max_n1 = 0;
+  long long total_keys = 0;  // length of the flattened key axis of this launch
+  for (int b = 0; b < B; ++b) {
+    if (seq_mask && !seq_mask[b]) continue;
+    const size_t i = (size_t)layer * B + b;
+    if (c->h_nd[i] + q_len > c->lay.cap)
+      return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: %d of %d decode slots used, %d more needed", b,
+                                           c->h_nd[i], c->lay.cap, q_len));
+    mask.w[b >> 6] |= 1ull << (b & 63);
+    ++n_active;
+    const int n1 = c->h_nd[i] + q_len;
+    total_keys += (long long)c->cfg.n_kv_heads * passes * (c->h_mlen[i] + n1);
+    if (n1 > max_n1) max_n1 = n1;
+  }
+  if (n_active == 0) return MKV_OK;
+  LayerView lv = layer_view(c, layer);
+  Scratch sc = scratch_view(c);
+  hipEvent_t* pe = nullptr;
+  KernelTimer t_attn, t_fin, t_ev;
+  if (c->prof.on) {
+    if (c->prof.used == Profiler::kSlots) {
+      hipError_t pe_err = prof_fold(c);
+      if (pe_err != hipSuccess) return fail_hip(c, pe_err, "profile events");
+    }
+    pe = &c->prof.ev[(size_t)c->prof.used * kEvPerSlot];
+    c->prof.evicted[c->prof.used] = 0;
+    t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
+  }
+  // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
+  // the caller fixed the range length
+  auto round64 = [](long long x) { return (x + 63) / 64 * 64; };
+  const int target = mq ? c->mq_target_groups : c->target_groups;
+  long long R = c->cfg.split_keys ? c->cfg.split_keys : round64((total_keys + target - 1) / target);
+  const long long r_min = round64((total_keys + c->lay.max_groups - 1) / c->lay.max_groups);
+  if (R < r_min) R = r_min;
+  if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
+  const int n_groups = (int)((total_keys + R - 1) / R);
+  hipError_t e;
+  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
+  else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
+  if (e != hipSuccess) return fail_hip(c, e, "attention launch");
+  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
+  else e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
+  if (e != hipSuccess) return fail_hip(c, e, "finish launch");
+  for (int b = 0; b < B; ++b) {
+    if (!mask.active(b)) continue;
+    const size_t i = (size_t)layer * B + b;
+    c->h_nd[i] += q_len;
+    c->h_step[i] += q_len;
+    c->frozen[i] = 1;
+    c->h_last_n[b] = c->h_nd[i];
+  }
+  c->last_layer = layer;
+  c->last_q_len = q_len;
+  int rc = MKV_OK;
+  if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
+    bool fired = false;
+    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr);
+    if (pe && fired) c->prof.evicted[c->prof.used] = 1;
+  }
+  if (pe) c->prof.used += 1;
+  return rc;
+}
+
 }  // namespace
 
 extern "C" {
@@ -262,6 +356,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   c->lay = make_layout(cfg);
   c->stream = (hipStream_t)cfg->stream;
   c->last_layer = -1;
+  c->last_q_len = 1;
   if (cfg->arena) {
     if (cfg->arena_bytes < c->lay.total) {
       std::string m = fmt("arena of %zu bytes given, %zu needed", cfg->arena_bytes, c->lay.total);
@@ -304,6 +399,14 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
     if (per_cu < 1) per_cu = 1;
     c->target_groups = cus * per_cu;
     if (c->target_groups > c->lay.max_groups) c->target_groups = c->lay.max_groups;
+    c->mq_target_groups = 0;
+    if (cfg->max_q_len > 0) {
+      int mq_per_cu = cfg->groups_per_cu;
+      if (mq_per_cu == 0 && e == hipSuccess) e = attn_mq_groups_per_cu(c->shape, &mq_per_cu);
+      if (mq_per_cu < 1) mq_per_cu = 1;
+      c->mq_target_groups = cus * mq_per_cu;
+      if (c->mq_target_groups > c->lay.max_groups) c->mq_target_groups = c->lay.max_groups;
+    }
   }
   // bookkeeping starts at zero: scores, positions, all lengths, the scratch
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
@@ -355,69 +458,16 @@ int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void
 
 int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, const void* v_new,
                     void* out, const uint8_t* seq_mask) {
+  return step(c, layer, 1, false, q, k_new, v_new, out, seq_mask);
+}
+
+int mkv_decode_step_multi(mkv_ctx* c, int layer, int q_len, const void* q, const void* k_new,
+                          const void* v_new, void* out, const uint8_t* seq_mask) {
   if (!c) return MKV_ERR_ARG;
-  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
-  if (!q || !k_new || !v_new || !out) return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must not be NULL");
-  const int B = c->cfg.batch;
-  SeqMask mask;
-  memset(&mask, 0, sizeof mask);
-  int n_active = 0, max_n1 = 0;
-  long long total_keys = 0;  // length of the flattened key axis of this launch
-  for (int b = 0; b < B; ++b) {
-    if (seq_mask && !seq_mask[b]) continue;
-    const size_t i = (size_t)layer * B + b;
-    if (c->h_nd[i] >= c->lay.cap)
-      return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: decode pool is full (%d slots)", b, c->lay.cap));
-    mask.w[b >> 6] |= 1ull << (b & 63);
-    ++n_active;
-    const int n1 = c->h_nd[i] + 1;
-    total_keys += (long long)c->cfg.n_kv_heads * c->lay.passes * (c->h_mlen[i] + n1);
-    if (n1 > max_n1) max_n1 = n1;
-  }
-  if (n_active == 0) return MKV_OK;
-  LayerView lv = layer_view(c, layer);
-  Scratch sc = scratch_view(c);
-  hipEvent_t* pe = nullptr;
-  KernelTimer t_attn, t_fin, t_ev;
-  if (c->prof.on) {
-    if (c->prof.used == Profiler::kSlots) {
-      hipError_t pe_err = prof_fold(c);
-      if (pe_err != hipSuccess) return fail_hip(c, pe_err, "profile events");
-    }
-    pe = &c->prof.ev[(size_t)c->prof.used * kEvPerSlot];
-    c->prof.evicted[c->prof.used] = 0;
-    t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
-  }
-  // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
-  // the caller fixed the range length
-  auto round64 = [](long long x) { return (x + 63) / 64 * 64; };
-  long long R = c->cfg.split_keys ? c->cfg.split_keys
-                                  : round64((total_keys + c->target_groups - 1) / c->target_groups);
-  const long long r_min = round64((total_keys + c->lay.max_groups - 1) / c->lay.max_groups);
-  if (R < r_min) R = r_min;
-  if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
-  const int n_groups = (int)((total_keys + R - 1) / R);
-  hipError_t e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
-  if (e != hipSuccess) return fail_hip(c, e, "attention launch");
-  e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
-  if (e != hipSuccess) return fail_hip(c, e, "finish launch");
-  for (int b = 0; b < B; ++b) {
-    if (!mask.active(b)) continue;
-    const size_t i = (size_t)layer * B + b;
-    c->h_nd[i] += 1;
-    c->h_step[i] += 1;
-    c->frozen[i] = 1;
-    c->h_last_n[b] = c->h_nd[i];
-  }
-  c->last_layer = layer;
-  int rc = MKV_OK;
-  if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
-    bool fired = false;
-    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr);
-    if (pe && fired) c->prof.evicted[c->prof.used] = 1;
-  }
-  if (pe) c->prof.used += 1;
-  return rc;
+  if (c->cfg.max_q_len == 0) return fail(c, MKV_ERR_STATE, "the context was created with max_q_len = 0");
+  if (q_len < 1 || q_len > c->cfg.max_q_len)
+    return fail(c, MKV_ERR_ARG, fmt("q_len %d outside [1, max_q_len = %d]", q_len, c->cfg.max_q_len));
+  return step(c, layer, q_len, true, q, k_new, v_new, out, seq_mask);
 }
 
 int mkv_evict(mkv_ctx* c, int layer, int seq) {
@@ -529,8 +579,11 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
   Scratch sc = scratch_view(c);
   hipError_t e = hipSuccess;
   if (abar && n) e = hipMemcpyAsync(abar, sc.abar + (size_t)seq * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
-  if (e == hipSuccess && lse_per_head)
-    e = hipMemcpyAsync(lse_per_head, sc.lse + (size_t)seq * c->cfg.n_q_heads, (size_t)c->cfg.n_q_heads * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && lse_per_head) {
+    // [B][q_len][H]: the last query row of the sequence
+    const size_t row = (size_t)seq * c->last_q_len + (c->last_q_len - 1);
+    e = hipMemcpyAsync(lse_per_head, sc.lse + row * c->cfg.n_q_heads, (size_t)c->cfg.n_q_heads * 4, hipMemcpyDeviceToHost, c->stream);
+  }
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "read probs");
   if (lse_per_head)

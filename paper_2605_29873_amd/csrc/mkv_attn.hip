@@ -7,6 +7,7 @@
 // multiply-adds (G = query heads per KV head), so the kernel is a bandwidth-bound stream over K
 // and V with the arithmetic on the vector ALU.
 #include "mkv_internal.h"
+#include "mkv_device.h"
 
 #include <hip/hip_ext.h>
 
@@ -18,56 +19,8 @@
 namespace mkv {
 namespace {
 
+using namespace dev;
 
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float x) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
-}
-
-// DPP controls: quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141, kDppMirror = 0x140;
-
-// Sum over the LPK adjacent lanes that share one key; every lane of the group gets the sum.
-template <int LPK>
-__device__ __forceinline__ float group_sum(float x) {
-  if constexpr (LPK >= 2) x += dpp_mov<kDppXor1>(x);
-  if constexpr (LPK >= 4) x += dpp_mov<kDppXor2>(x);
-  if constexpr (LPK >= 8) x += dpp_mov<kDppHalfMirror>(x);
-  if constexpr (LPK >= 16) x += dpp_mov<kDppMirror>(x);
-  return x;
-}
-
-// Reductions across the 64/LPK key groups of a wave.  Lane c of every group takes part with lane c
-// of the others (row rotations by multiples of LPK, then the two cross-row exchanges), so the same
-// code serves values that are uniform inside a group and per-lane accumulators.
-constexpr int kDppRowRor = 0x120;
-template <int LPK>
-__device__ __forceinline__ float across_groups_max(float x) {
-  if constexpr (LPK <= 1) x = fmaxf(x, dpp_mov<kDppRowRor + 1>(x));
-  if constexpr (LPK <= 2) x = fmaxf(x, dpp_mov<kDppRowRor + 2>(x));
-  if constexpr (LPK <= 4) x = fmaxf(x, dpp_mov<kDppRowRor + 4>(x));
-  if constexpr (LPK <= 8) x = fmaxf(x, dpp_mov<kDppRowRor + 8>(x));
-  x = fmaxf(x, __shfl_xor(x, 16));
-  x = fmaxf(x, __shfl_xor(x, 32));
-  return x;
-}
-template <int LPK>
-__device__ __forceinline__ float across_groups_sum(float x) {
-  if constexpr (LPK <= 1) x += dpp_mov<kDppRowRor + 1>(x);
-  if constexpr (LPK <= 2) x += dpp_mov<kDppRowRor + 2>(x);
-  if constexpr (LPK <= 4) x += dpp_mov<kDppRowRor + 4>(x);
-  if constexpr (LPK <= 8) x += dpp_mov<kDppRowRor + 8>(x);
-  x += __shfl_xor(x, 16);
-  x += __shfl_xor(x, 32);
-  return x;
-}
-
-__device__ __forceinline__ uint4 ldg16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
-__device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // <k, q> over one 16-byte vector, added to acc.  bf16: two products per v_dot2c_f32_bf16
 // (products of bf16 pairs are exact in fp32; the sum is fp32).
@@ -116,44 +69,6 @@ struct AttnArgs {
   int R;       // keys per work-group: the flattened key axis is cut into equal ranges
   int* occupancy;  // host pointer, only for the occupancy query
 };
-
-// quad_perm controls that exchange lane i with lane i^K inside every group of four lanes
-template <int K>
-__device__ __forceinline__ float quad_xor(float x) {
-  if constexpr (K == 1) return dpp_mov<0xB1>(x);       // [1,0,3,2]
-  else if constexpr (K == 2) return dpp_mov<0x4E>(x);  // [2,3,0,1]
-  else if constexpr (K == 3) return dpp_mov<0x1B>(x);  // [3,2,1,0]
-  else return x;
-}
-
-// Prefix sums of the per-sequence key counts, built by one wave into LDS: offs[b] = number of keys
-// of all units of sequences < b, where a sequence has `units` = Hkv * passes units of
-// L_b = M_b + n_d + 1 keys each (0 for inactive sequences).  Returns nothing; offs has B+1 entries.
-__device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& lv, const SeqMask& mask,
-                                              int units, long long* offs, int lane) {
-  const int per = (s.B + 63) / 64;
-  const int b0 = lane * per;
-  long long sum = 0;
-  for (int i = 0; i < per; ++i) {
-    const int b = b0 + i;
-    if (b < s.B && mask.active(b)) sum += (long long)units * (lv.mlen[b] + lv.nd[b] + 1);
-  }
-  long long incl = sum;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const long long y = __shfl_up(incl, off);
-    if (lane >= off) incl += y;
-  }
-  long long run = incl - sum;
-  for (int i = 0; i < per; ++i) {
-    const int b = b0 + i;
-    if (b < s.B) {
-      offs[b] = run;
-      if (mask.active(b)) run += (long long)units * (lv.mlen[b] + lv.nd[b] + 1);
-    }
-  }
-  if (lane == 63) offs[s.B] = incl;
-}
 
 // Work-group k streams the keys [k*R, (k+1)*R) of the FLATTENED key axis -- sequence by sequence,
 // inside a sequence unit by unit (unit = one KV head x one pass of up to HL of its query heads),
@@ -206,7 +121,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   constexpr int WT = 6144 / (HL * TK);   // decode tiles per logit staging window (24 KiB of LDS)
   constexpr int SK = WT * TK;            // keys per window
   __shared__ float sm_logit[HL][SK];
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, offs, lane);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1, offs, lane);
   __syncthreads();
   if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -572,12 +487,6 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   }
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
-  uint32_t u = __builtin_bit_cast(uint32_t, x);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-
 struct FinishArgs {
   Shape s;
   LayerView lv;
@@ -589,17 +498,6 @@ struct FinishArgs {
 };
 
 constexpr int kFinishThreads = 256;
-
-__device__ __forceinline__ float wave_max(float x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x = fmaxf(x, __shfl_xor(x, off));
-  return x;
-}
-__device__ __forceinline__ float wave_sum(float x) {
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) x += __shfl_xor(x, off);
-  return x;
-}
 
 // Where the attention kernel left the partials of query head h of sequence b: first slot, number
 // of slots, and the head's position inside a slot.
@@ -615,19 +513,6 @@ __device__ __forceinline__ PieceSpan piece_span(const Shape& s, const long long*
   p.ns = (int)(kl - kf) + 1;
   p.hs = hl - pass * s.HL;
   return p;
-}
-
-// Softmax normaliser of one head from its per-piece (reference, sum) pairs, by one whole wave:
-// returns the common reference mx and the total sum L relative to it (both base 2).  `ml` points
-// at the head's pair in the first slot; consecutive slots are `stride` floats apart.
-__device__ __forceinline__ void wave_merge_ml(const float* ml, int stride, int ns, int lane, float& mx, float& L) {
-  float m_loc = -INFINITY;
-  for (int i = lane; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[(size_t)i * stride]);
-  mx = wave_max(m_loc);
-  float l_loc = 0.f;
-  for (int i = lane; i < ns; i += 64)
-    l_loc = fmaf(fast_exp2(ml[(size_t)i * stride] - mx), ml[(size_t)i * stride + 1], l_loc);
-  L = wave_sum(l_loc);
 }
 
 // grid (H + ceil(max n_d / 256), B).  Blocks x < H merge the partials of head x and write Att_t

@@ -46,12 +46,14 @@ struct LayerView {
 
 // Per-step scratch, shared by all layers (layers run one after another on one stream).
 struct Scratch {
-  float* part_o;      // [max_groups + B*Hkv*passes][HL][D]  un-normalised partial outputs per piece
-  float* part_ml;     // [max_groups + B*Hkv*passes][HL][2]  (reference, sum) per piece, base-2 units
+  // per piece: un-normalised partial outputs and (reference, sum) pairs in base-2 units; HL rows
+  // per slot in the single-query kernels, 16 in the multi-query ones
+  float* part_o;      // [max_groups + B*Hkv*passes][HL][D]
+  float* part_ml;     // [max_groups + B*Hkv*passes][HL][2]
   long long* offs;    // [B+1]  prefix sums of the per-sequence key counts of the last launch
-  float* logits;      // [B][H][cap]       base-2 logits of decode keys
+  float* logits;      // [B][H*q_len][cap] base-2 logits of decode keys (q_len = 1 in the single-query step)
   float* abar;        // [B][cap]          head-mean decode-slice attention of the last step
-  float* lse;         // [B][H]            base-2 log of the softmax normaliser of the last step
+  float* lse;         // [B][q_len][H]     base-2 log of the softmax normaliser of the last step
   int32_t* src_map;   // [B][cap]          compaction map: new slot -> old slot
   int32_t* evict_info;  // [B][2]          (first moved slot, new pool size) of the last selection
 };
@@ -76,6 +78,17 @@ hipError_t launch_finish(const Shape& s, const LayerView& lv, const Scratch& sc,
 // Evicts every masked sequence whose pool size exceeds `threshold` back to s.budget.
 hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
                         int threshold, hipStream_t st, const KernelTimer* tm = nullptr);
+
+// Multi-query step (bf16, head_dim 128): q_len query rows per sequence on the matrix cores.
+// A pass serves mq_heads_per_pass(G, q_len) query heads x q_len rows <= 16 rows per KV head.
+int mq_heads_per_pass(int G, int q_len);
+hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
+                          const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
+                          int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
+hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
+hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
+                            const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
+                            const KernelTimer* tm = nullptr);
 
 hipError_t configure_kernels();
 

@@ -30,7 +30,8 @@ def from_device(t: torch.Tensor) -> np.ndarray:
 
 
 def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = None,
-             split_keys: int = 0, max_prefill: int | None = None, stream: int | None = None):
+             split_keys: int = 0, max_prefill: int | None = None, stream: int | None = None,
+             max_q_len: int = 0, attn_variant: int = 0):
     cfg = mkv.make_config(
         n_layers=wl.n_layers if layers is None else layers, batch=wl.batch,
         n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
@@ -38,8 +39,9 @@ def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = No
         max_prefill=wl.prefill_max if max_prefill is None else max_prefill,
         decode_budget=wl.decode_budget,
         evict_trigger=mkv.MKV_NEVER_EVICT if manual_evict else wl.evict_trigger,
-        decode_capacity=wl.capacity, recent_window=wl.recent_window, alpha=wl.alpha,
-        softmax_scale=0.0, score_mode=mkv.MKV_SCORE_LAYER_MEAN, split_keys=split_keys,
+        decode_capacity=wl.capacity + max(0, max_q_len - 1), recent_window=wl.recent_window,
+        alpha=wl.alpha, softmax_scale=0.0, score_mode=mkv.MKV_SCORE_LAYER_MEAN,
+        split_keys=split_keys, max_q_len=max_q_len, attn_variant=attn_variant,
         stream=stream if stream is not None else torch.cuda.current_stream().cuda_stream)
     return mkv.mkv_create(cfg)
 
@@ -59,7 +61,8 @@ class Lockstep:
     identical scores, and the decision must then match bit for bit."""
 
     def __init__(self, mkv, wl: X.Workload, layer: int = 0, split_keys: int = 0, seqs=None,
-                 active=None, n_layers: int | None = None, device_fill_unfollowed: bool = False):
+                 active=None, n_layers: int | None = None, device_fill_unfollowed: bool = False,
+                 max_q_len: int = 0, attn_variant: int = 0):
         """seqs: the sequences the oracle follows (default: all); active: the sequences the GPU
         steps (default: seqs).  Sequences that are active but not followed load the GPU at the
         real batch size; they evict through the library's own trigger check."""
@@ -69,7 +72,7 @@ class Lockstep:
         assert set(self.seqs) <= set(self.active)
         self.device_fill = device_fill_unfollowed   # unfollowed sequences: values drawn on the device
         self.ctx = make_ctx(mkv, wl, manual_evict=True, layers=layer + 1 if n_layers is None else n_layers,
-                            split_keys=split_keys)
+                            split_keys=split_keys, max_q_len=max_q_len, attn_variant=attn_variant)
         self.oracles = {s: oracle_state(wl) for s in self.seqs}
         self.out = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim),
                                dtype=torch.bfloat16 if wl.dtype == "bf16" else torch.float32,
@@ -160,7 +163,41 @@ class Lockstep:
                     f"step {t} seq {s}: abar mismatch"
             if check_scores:
                 self.check_scores(s)
-        # capacity check (Eq. 7 with the trigger): both sides evict on the oracle's float32 scores
+        self.capacity_check(t)
+
+    def step_multi(self, t0: int, q_len: int, check_scores: bool = True, check_abar: bool = False):
+        """q_len steps in one library call; the oracle takes them one by one (Algorithm 1 per
+        token) with its capacity check held back to the end of the chunk."""
+        wl = self.wl
+        per_step = [X.step_batch(wl, self.layer, t0 + i) for i in range(q_len)]
+        q, k, v = (np.stack([p[r] for p in per_step], axis=1) for r in range(3))   # [B, q_len, heads, D]
+        dq, dk, dv = (to_device(a, wl.dtype) for a in (q, k, v))
+        out = torch.zeros((wl.batch, q_len, wl.n_q_heads, wl.head_dim), dtype=self.out.dtype, device="cuda")
+        self.mkv.mkv_decode_step_multi(self.ctx, self.layer, q_len, dq.data_ptr(), dk.data_ptr(),
+                                       dv.data_ptr(), out.data_ptr(), self.mask)
+        torch.cuda.synchronize()
+        got = from_device(out)
+        rtol, atol = OUT_TOL[wl.dtype]
+        for s in self.seqs:
+            st = self.oracles[s]
+            for i in range(q_len):
+                ref, abar = st.decode_step(q[s, i], k[s, i], v[s, i], auto_evict=False)
+                err = np.abs(got[s, i] - ref)
+                self.max_out_err = max(self.max_out_err, float(err.max()))
+                assert np.all(err <= atol + rtol * np.abs(ref)), \
+                    f"step {t0}+{i} seq {s}: attention output off by {err.max():.3e}"
+            if check_abar:     # of the last row
+                ga, _ = self.mkv.mkv_read_probs(self.ctx, self.layer, s, wl.n_q_heads, wl.capacity + q_len)
+                assert ga.shape == abar.shape
+                assert np.all(np.abs(ga - abar) <= SCORE_RTOL * abar + SCORE_ATOL), \
+                    f"step {t0}+{q_len - 1} seq {s}: abar mismatch"
+            if check_scores:
+                self.check_scores(s)
+        self.capacity_check(t0 + q_len - 1)
+
+    def capacity_check(self, t: int):
+        """Eq. 7 with the trigger: both sides evict on the oracle's float32 scores."""
+        wl = self.wl
         for s in self.active:
             if s not in self.oracles:
                 _, n_d, _ = self.mkv.mkv_get_lens(self.ctx, self.layer, s)

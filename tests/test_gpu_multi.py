@@ -1,0 +1,153 @@
+"""GPU parity of the multi-query step (q_len tokens per call on the matrix cores) against the CPU
+oracle taking the same tokens one Algorithm-1 step at a time, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_29873_amd import inputs as X
+from tests.harness import Lockstep, make_ctx
+
+pytestmark = pytest.mark.gpu
+
+WL = X.workloads()
+
+
+def _chunks(ls, tokens, q_lens, t0=0, **kw):
+    """Feeds `tokens` tokens in calls of the given lengths (cycled)."""
+    try:
+        t, i = t0, 0
+        while t < t0 + tokens:
+            n = q_lens[i % len(q_lens)]
+            if n == 0:
+                ls.step(t, **kw)
+                t += 1
+            else:
+                ls.step_multi(t, n, **kw)
+                t += n
+            i += 1
+        for s in ls.seqs:
+            ls.check_prefill_untouched(s)
+    finally:
+        ls.close()
+
+
+def _small(G, Hkv, **kw):
+    base = dict(batch=2, n_layers=1, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=128, dtype="bf16",
+                prefill_min=50, prefill_max=333, decode_budget=20, evict_trigger=27, recent_window=3,
+                alpha=0.65, steps=0, hh_prob=0.05)
+    base.update(kw)
+    return X.Workload("multi", **base)
+
+
+@pytest.mark.parametrize("G,Hkv,Q", [
+    (4, 2, 4),     # Llama grouping: 16 rows, one pass
+    (4, 2, 1),     # single query on the matrix-core kernel: 4 of 16 rows used
+    (7, 1, 2),     # Qwen grouping: 14 rows
+    (7, 2, 1),
+    (8, 1, 2),     # exactly 16 rows
+    (1, 2, 16),    # no grouping, 16 query positions
+    (2, 2, 8),
+    (4, 1, 8),     # two heads per pass, two passes
+    (3, 2, 5),     # 15 rows
+    (12, 1, 3),    # five heads per pass, three passes, the last with two heads
+])
+@pytest.mark.parametrize("split_keys", [0, 64])
+def test_chunked_decode_matches_token_by_token_oracle(mkv, G, Hkv, Q, split_keys):
+    wl = _small(G, Hkv)
+    ls = Lockstep(mkv, wl, split_keys=split_keys, max_q_len=Q)
+    ls.prefill()
+    _chunks(ls, 70 if Q > 1 else 40, [Q], check_abar=True)
+    assert ls.evictions >= 4
+
+
+def test_call_lengths_may_vary_and_mix_with_single_steps(mkv):
+    # 0 = the single-query entry point; the pool crosses the trigger at different offsets
+    wl = _small(4, 2, decode_budget=33, evict_trigger=40, recent_window=0, alpha=0.9)
+    ls = Lockstep(mkv, wl, split_keys=64, max_q_len=7)
+    ls.prefill()
+    _chunks(ls, 150, [3, 0, 7, 1, 0, 0, 5, 2], check_abar=True)
+    assert ls.evictions >= 10
+
+
+def test_empty_prefill_and_empty_pool(mkv):
+    # the first call sees nothing but its own tokens: row i attends to tokens 0..i only
+    wl = _small(4, 1, prefill_min=0, prefill_max=0, batch=1)
+    ls = Lockstep(mkv, wl, max_q_len=4)
+    ls.prefill()
+    _chunks(ls, 48, [4], check_abar=True)
+
+
+@pytest.mark.parametrize("G,Q", [(4, 4), (7, 2)])
+def test_decode_pool_longer_than_one_logit_window(mkv, G, Q):
+    # the kernel stages decode logits in LDS windows of 384 keys
+    n_d = 1000
+    wl = _small(G, 2, decode_budget=n_d, evict_trigger=n_d + 5, recent_window=5, alpha=0.9, hh_prob=0.02)
+    for split in (0, 64):
+        ls = Lockstep(mkv, wl, split_keys=split, max_q_len=Q)
+        ls.prefill()
+        ls.load_snapshot(n_d - 1, 3 * n_d)
+        _chunks(ls, 4 * Q, [Q], t0=3 * n_d, check_abar=True)
+        assert ls.evictions >= 2
+
+
+def test_cfg3_ragged_batch_full_size_sampled_chunks_of_4(mkv):
+    # all 16 ragged sequences in the automatic launch configuration, three followed by the oracle
+    wl = WL["cfg3"]
+    ls = Lockstep(mkv, wl, seqs=[0, 7, 13], active=range(wl.batch), max_q_len=4)
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 6, 5000)
+    _chunks(ls, 12, [4], t0=5000)
+    assert ls.evictions == 3
+    print(f"cfg3 q_len 4: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
+def test_cfg4_qwen_single_query_on_matrix_cores(mkv):
+    wl = WL["cfg4"]
+    ls = Lockstep(mkv, wl, seqs=[2, 5], active=range(wl.batch), max_q_len=2)
+    ls.prefill()
+    ls.load_snapshot(wl.decode_budget - 2, 9000)
+    _chunks(ls, 8, [1, 2], t0=9000)
+    assert ls.evictions >= 2 * 4
+
+
+def test_inactive_sequences_are_left_alone(mkv):
+    wl = _small(4, 2, batch=3)
+    ls = Lockstep(mkv, wl, seqs=[0, 2], max_q_len=4)
+    ls.prefill()
+    _chunks(ls, 24, [4])
+    ctx = make_ctx(mkv, wl, manual_evict=True, max_q_len=4)
+    try:
+        assert mkv.mkv_get_lens(ctx, 0, 1) == (0, 0, 0)
+    finally:
+        mkv.mkv_destroy(ctx)
+
+
+def test_argument_and_state_errors(mkv):
+    wl = _small(4, 2)
+    z = torch.zeros(2 * 16 * 8 * 128, dtype=torch.bfloat16, device="cuda")
+    ctx = make_ctx(mkv, wl, manual_evict=True)            # max_q_len = 0
+    try:
+        with pytest.raises(mkv.MkvError) as e:
+            mkv.mkv_decode_step_multi(ctx, 0, 2, z.data_ptr(), z.data_ptr(), z.data_ptr(), z.data_ptr())
+        assert e.value.code == mkv.MKV_ERR_STATE
+    finally:
+        mkv.mkv_destroy(ctx)
+    ctx = make_ctx(mkv, wl, manual_evict=True, max_q_len=4)
+    try:
+        for bad in (0, 5, -1):
+            with pytest.raises(mkv.MkvError) as e:
+                mkv.mkv_decode_step_multi(ctx, 0, bad, z.data_ptr(), z.data_ptr(), z.data_ptr(), z.data_ptr())
+            assert e.value.code == mkv.MKV_ERR_ARG
+        # capacity = 28 + 3 slots: seven calls of 4 fit, the eighth does not (no eviction here)
+        for _ in range(7):
+            mkv.mkv_decode_step_multi(ctx, 0, 4, z.data_ptr(), z.data_ptr(), z.data_ptr(), z.data_ptr())
+        with pytest.raises(mkv.MkvError) as e:
+            mkv.mkv_decode_step_multi(ctx, 0, 4, z.data_ptr(), z.data_ptr(), z.data_ptr(), z.data_ptr())
+        assert e.value.code == mkv.MKV_ERR_CAPACITY
+        assert mkv.mkv_get_lens(ctx, 0, 0)[1] == 28
+    finally:
+        mkv.mkv_destroy(ctx)
+    with pytest.raises(mkv.MkvError):
+        make_ctx(mkv, X.scaled(wl, dtype="f32"), manual_evict=True, max_q_len=2)
+    with pytest.raises(mkv.MkvError):
+        make_ctx(mkv, X.scaled(wl, head_dim=64), manual_evict=True, max_q_len=2)
