@@ -29,7 +29,8 @@ struct Layout {
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, total;
   int cap, HL, passes, max_groups;
-  int mq_passes;          // most passes per KV head of a multi-query step (0: entry point disabled)
+  int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
+  bool mfma_single;       // mkv_decode_step runs on the matrix-core kernels
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
 };
 
@@ -89,8 +90,14 @@ Layout make_layout(const mkv_config* c) {
   L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + grow;
   L.HL = head_lanes(G);
   L.passes = (G + L.HL - 1) / L.HL;
-  if (c->max_q_len > 0) {
-    const int hp = mq_heads_per_pass(G, c->max_q_len);   // fewest heads per pass = most passes
+  // Single-query steps of bf16 x 128 layers with more than four query heads per KV head go to the
+  // matrix-core kernels too: the vector-ALU kernel spends G multiply-adds per loaded element and
+  // falls behind the memory stream there (measured on G = 7: 3.7 -> 4.9 TB/s).  attn_variant
+  // 1..15 forces the vector-ALU kernel, 16.. the matrix-core one.
+  const bool mfma_ok = c->dtype == MKV_BF16 && c->head_dim == 128;
+  L.mfma_single = mfma_ok && (c->attn_variant >= 16 || (c->attn_variant == 0 && G > 4));
+  if (c->max_q_len > 0 || L.mfma_single) {
+    const int hp = mq_heads_per_pass(G, grow);           // fewest heads per pass = most passes
     L.mq_passes = (G + hp - 1) / hp;
   }
   const size_t es = c->dtype == MKV_BF16 ? 2 : 4;
@@ -400,7 +407,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
     c->target_groups = cus * per_cu;
     if (c->target_groups > c->lay.max_groups) c->target_groups = c->lay.max_groups;
     c->mq_target_groups = 0;
-    if (cfg->max_q_len > 0) {
+    if (c->lay.mq_passes > 0) {
       int mq_per_cu = cfg->groups_per_cu;
       if (mq_per_cu == 0 && e == hipSuccess) e = attn_mq_groups_per_cu(c->shape, &mq_per_cu);
       if (mq_per_cu < 1) mq_per_cu = 1;
@@ -458,7 +465,7 @@ int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void
 
 int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, const void* v_new,
                     void* out, const uint8_t* seq_mask) {
-  return step(c, layer, 1, false, q, k_new, v_new, out, seq_mask);
+  return step(c, layer, 1, c && c->lay.mfma_single, q, k_new, v_new, out, seq_mask);
 }
 
 int mkv_decode_step_multi(mkv_ctx* c, int layer, int q_len, const void* q, const void* k_new,

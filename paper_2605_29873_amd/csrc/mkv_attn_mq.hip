@@ -28,9 +28,7 @@ constexpr int kD = 128;
 constexpr int kRowB = kD * 2;      // bytes per K or V row
 constexpr int kNV = kRowB / 16;    // 16-byte vectors per row
 constexpr int kTK = 32;            // keys per wave tile
-constexpr int kSK = 384;           // decode keys per logit staging window
-constexpr int kSKP = kSK + 4;      // padded LDS row: spreads the 16 rows over the banks
-constexpr int kWT = kSK / kTK;     // tiles per window
+constexpr int kLogitFloats = 6144;  // LDS floats that stage decode logits: nrows x (keys per window)
 
 struct MqArgs {
   Shape s;
@@ -48,6 +46,24 @@ struct MqArgs {
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
 
+// c ? x : y on values.  (A conditional between two captured variables is an lvalue, i.e. a choice
+// between two addresses followed by a load, which keeps the variables in memory.)
+template <typename T>
+__device__ __forceinline__ T pick(bool c, T x, T y) { return c ? x : y; }
+template <typename T>
+__device__ __forceinline__ T pick3(int seg, T x0, T x1, T x2) { return pick(seg == 0, x0, pick(seg == 1, x1, x2)); }
+
+// Untyped buffer descriptor over `bytes` bytes at p: loads past the end return zeros.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* p, int bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
+}
+// 16 bytes at (lane offset + scalar offset) of the buffer
+__device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_t wave_off) {
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_off, wave_off, 0));
+}
+
 // Same partition of the flattened key axis as the single-query kernel: work-group k takes keys
 // [k*R, (k+1)*R), a unit is one KV head x one pass, and every piece of a unit leaves a partial
 // (reference, sum, sum p*V) per row in slot  k + unit index.  A unit has L = M + n_d + Q keys.
@@ -60,20 +76,30 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin
 // The V^T operand wants, per lane, one head-dim element of 8 keys: lane (r, j) loads vector r of
 // the 8 keys it contracts and transposes 16-bit halves in registers (one byte-permute per dword).
 // The accumulators then hold O[row r][8 * (4j + i) + dc] for chunk dc, i = 0..3.
+#ifdef MKV_TIMELINE
+// Tuning builds: wall-clock stamps (100 MHz) per work-group at five points of the kernel.
+__device__ unsigned long long g_timeline[8192 * 8];
+#define MKV_STAMP(i) do { if (tid == 0 && blockIdx.x < 8192) g_timeline[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
+#else
+#define MKV_STAMP(i) do {} while (0)
+#endif
+
 template <int WPB>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   constexpr int kThreads = WPB * 64;
   const Shape& s = a.s;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = uniform(tid >> 6);   // tile indices stay scalar
   const int r16 = lane & 15;
   const int j4 = lane >> 4;
   const int Q = a.Q;
   const int units = s.Hkv * a.passes;
 
+  MKV_STAMP(0);
   __shared__ long long offs[kMaxBatch + 1];
-  __shared__ float sm_logit[16][kSKP];
+  __shared__ float sm_logit[kLogitFloats + 16 * 4];   // rows of SK + 4 floats (the pad spreads the banks)
+  __shared__ float sm_new[16][kTK + 4];      // logits of the appended tokens
   __shared__ float sm_part[WPB / 2][34][64];   // a wave's accumulators, reference and sum, lane-major
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane);
   __syncthreads();
@@ -83,54 +109,65 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       if (b < s.B && a.mask.active(b)) a.lv.nd_eff[b] = a.lv.nd[b] + Q;
     }
   }
-  const long long total = offs[s.B];
+  const long long total = uniform(offs[s.B]);
   long long r0 = (long long)blockIdx.x * a.R;
   const long long r1 = min(total, r0 + a.R);
   if (r0 >= r1) return;
+  MKV_STAMP(1);
 
   int b;
   {
     int lo = 0, hi = s.B;
     while (hi - lo > 1) {
       const int mid = (lo + hi) >> 1;
-      if (offs[mid] <= r0) lo = mid; else hi = mid;
+      if (uniform(offs[mid]) <= r0) lo = mid; else hi = mid;
     }
-    b = lo;
+    b = uniform(lo);
   }
 
   while (r0 < r1) {
-    while (offs[b + 1] <= r0) ++b;
-    const int M = a.lv.mlen[b];
-    const int n0 = a.lv.nd[b];
+    while (uniform(offs[b + 1]) <= r0) ++b;
+    b = uniform(b);
+    const long long ob = uniform(offs[b]);
+    const int M = uniform(a.lv.mlen[b]);
+    const int n0 = uniform(a.lv.nd[b]);
     const int n1 = n0 + Q;
     const int L = M + n1;
-    const int ul = (int)((r0 - offs[b]) / L);
+    const int ul = uniform((int)((r0 - ob) / L));   // (the 64-bit division runs on the vector ALU)
     const int g = ul / a.passes;
     const int pass = ul - g * a.passes;
-    const int ka = (int)(r0 - offs[b] - (long long)ul * L);
-    const int ke = (int)min((long long)L, ka + (r1 - r0));
+    const int ka = uniform((int)(r0 - ob - (long long)ul * L));
+    const int ke = uniform((int)min((long long)L, ka + (r1 - r0)));
     const int p0 = min(ka, M), p1 = min(ke, M);
     const int d0 = max(ka, M) - M, d1 = max(ke, M) - M;
+    // three kinds of tiles: prefill keys [p0, p1); decode keys that are in the pool already
+    // [d0, dp); and appended tokens [a0, d1) of this call, which are still in k_new / v_new
+    const int dp = min(d1, n0);
+    const int a0 = max(d0, n0);
     const int ntp = (p1 - p0 + kTK - 1) / kTK;
-    const int ntd = (d1 - d0 + kTK - 1) / kTK;
-    const int ntile = ntp + ntd;
+    const int ntd = (max(dp - d0, 0) + kTK - 1) / kTK;
+    const int nta = d1 > a0 ? 1 : 0;                       // Q <= 16 < kTK: one tile holds them
+    const int ntile = ntp + ntd + nta;
     const int nrows = min(a.HP, s.G - pass * a.HP) * Q;   // real rows of this pass
+    // logit staging window: as many keys as the real rows leave room for (whole tiles)
+    const int SK = (kLogitFloats / nrows) & ~(kTK - 1);
+    const int WT = SK / kTK;
+    const int SKP = SK + 4;
 
-    const size_t head_row = (size_t)b * s.Hkv + g;
+    const size_t head_row = (size_t)uniform(b * s.Hkv + g);
     const char* kpre = (const char*)a.lv.Kp + head_row * (size_t)s.pstride * kRowB;
     const char* vpre = (const char*)a.lv.Vp + head_row * (size_t)s.pstride * kRowB;
     const char* kdec = (const char*)a.lv.Kd + head_row * (size_t)s.dstride * kRowB;
     const char* vdec = (const char*)a.lv.Vd + head_row * (size_t)s.dstride * kRowB;
     // appended token qn of this KV head: row (b, qn, g) of k_new / v_new
-    const size_t new_stride = (size_t)s.Hkv * kRowB;
+    const int new_stride = s.Hkv * kRowB;
     const char* knew = a.k_new + ((size_t)b * Q * s.Hkv + g) * kRowB;
     const char* vnew = a.v_new + ((size_t)b * Q * s.Hkv + g) * kRowB;
 
     // Append (Alg. 1): the work-group whose piece holds new slots stores their rows for later
     // steps; in this step every reader takes them from k_new / v_new.
     if (pass == 0) {
-      const int a0 = max(d0, n0), a1 = min(d1, n1);
-      for (int idx = tid; idx < (a1 - a0) * 2 * kNV; idx += kThreads) {
+      for (int idx = tid; idx < (d1 - a0) * 2 * kNV; idx += kThreads) {
         const int row = idx / (2 * kNV), rem = idx - row * 2 * kNV;
         const int vsel = rem / kNV, vec = rem - vsel * kNV;
         const int jn = a0 + row;
@@ -140,7 +177,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
       if (g == 0) {
         const int t0 = a.lv.tpos[b];
-        for (int idx = tid; idx < a1 - a0; idx += kThreads)
+        for (int idx = tid; idx < d1 - a0; idx += kThreads)
           a.lv.pos[(size_t)b * s.cap + a0 + idx] = t0 + (a0 + idx - n0);
       }
     }
@@ -161,35 +198,51 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
 #pragma unroll
     for (int dc = 0; dc < 8; ++dc) acc[dc] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    // K and V come in through buffer loads: a wave-uniform descriptor per segment whose size ends
+    // at the segment's last valid row -- rows past it read as zeros, so no lane clamps or branches
+    // -- plus one lane offset per operand; the tile's position is a scalar offset.
+    //   K: lane (r, j) reads vectors 4*iv + j of row r of each 16-key half
+    //   V: lane (r, j) reads vector r of rows 4j + i of each half
+    const uint32_t vk_pool = r16 * kRowB + j4 * 16, vv_pool = 4 * j4 * kRowB + r16 * 16;
+    const uint32_t vk_new = r16 * new_stride + j4 * 16, vv_new = 4 * j4 * new_stride + r16 * 16;
+
+    // where tile tt starts: segment (0 prefill, 1 pool, 2 appended) and first key of the tile,
+    // counted inside the prefill pool or the decode pool
+    auto tile_seg = [&](int tt) __attribute__((always_inline)) { return tt < ntp ? 0 : (tt < ntp + ntd ? 1 : 2); };
+    auto tile_key = [&](int tt, int seg) __attribute__((always_inline)) {
+      return pick3(seg, p0 + tt * kTK, d0 + (tt - ntp) * kTK, a0 + 0);
+    };
+
+    const int new_rows = d1 - n0;                           // appended tokens this piece may read
+    const int bytes_pre = p1 * kRowB, bytes_dec = max(dp, 0) * kRowB;
+    const int bytes_new = new_rows > 0 ? (new_rows - 1) * new_stride + kRowB : 0;
+
     auto load_tile = [&](int tt, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) __attribute__((always_inline)) {
-      const bool dec = tt >= ntp;
-      const int jb = dec ? d0 + (tt - ntp) * kTK : p0 + tt * kTK;
-      const int jl = (dec ? d1 : p1) - 1;
-      const char* kbase = dec ? kdec : kpre;
-      const char* vbase = dec ? vdec : vpre;
+      const int seg = tile_seg(tt);
+      const int jb = tile_key(tt, seg);
+      const int bytes = pick3(seg, bytes_pre, bytes_dec, bytes_new);
+      const rsrc_t rk = make_rsrc(pick3(seg, kpre, kdec, knew), bytes);
+      const rsrc_t rv = make_rsrc(pick3(seg, vpre, vdec, vnew), bytes);
+      const int stride = pick(seg == 2, new_stride, kRowB);
+      const int row0 = pick(seg == 2, jb - n0, jb);                   // first row of the tile in its array
+      const uint32_t vk = pick(seg == 2, vk_new, vk_pool);
+      const uint32_t vv = pick(seg == 2, vv_new, vv_pool);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const int jk = min(jb + 16 * h + r16, jl);          // clamp: masked later
-        const bool knw = dec && jk >= n0;
-        const char* kp = knw ? knew + (size_t)(jk - n0) * new_stride : kbase + (size_t)jk * kRowB;
+        const uint32_t so = (uint32_t)(row0 + 16 * h) * (uint32_t)stride;
 #pragma unroll
-        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = ldg16(kp + (4 * iv + j4) * 16);
+        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = buf_load16(rk, vk + iv * 64, so);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int jv = min(jb + 16 * h + 4 * j4 + i, jl);
-          const bool vnw = dec && jv >= n0;
-          const char* vp = vnw ? vnew + (size_t)(jv - n0) * new_stride : vbase + (size_t)jv * kRowB;
-          vr[h][i] = ldg16(vp + r16 * 16);
-        }
+        for (int i = 0; i < 4; ++i) vr[h][i] = buf_load16(rv, vv, so + (uint32_t)(i * stride));
       }
     };
 
     int win = 0;
     constexpr float kSlack = 8.0f;
     auto compute_tile = [&](int tt, const uint4 (&kr)[2][4], const uint4 (&vr)[2][4]) __attribute__((always_inline)) {
-      const bool dec = tt >= ntp;
-      const int jb = dec ? d0 + (tt - ntp) * kTK : p0 + tt * kTK;
-      const int jn = dec ? d1 : p1;
+      const int seg = tile_seg(tt);
+      const int jb = tile_key(tt, seg);
+      const int jn = pick3(seg, p1, dp, d1);
       float x[8];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
@@ -201,13 +254,14 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         float4 st;
         st.x = sv[0] * s.scale_log2; st.y = sv[1] * s.scale_log2;
         st.z = sv[2] * s.scale_log2; st.w = sv[3] * s.scale_log2;
-        if (dec) *reinterpret_cast<float4*>(&sm_logit[r16][(tt - ntp - win * kWT) * kTK + 16 * h + 4 * j4]) = st;
+        if (seg == 1 && r16 < nrows) *reinterpret_cast<float4*>(&sm_logit[r16 * SKP + (tt - ntp - win * WT) * kTK + 16 * h + 4 * j4]) = st;
+        if (seg == 2) *reinterpret_cast<float4*>(&sm_new[r16][16 * h + 4 * j4]) = st;
         const float sx[4] = {st.x, st.y, st.z, st.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const int key = key0 + i;
-          // past the piece, or an appended token that comes after this row's own (causal order)
-          const bool ok = key < jn && !(dec && key - n0 > qi);
+          // past the segment, or an appended token that comes after this row's own (causal order)
+          const bool ok = key < jn && !(seg == 2 && key - n0 > qi);
           x[4 * h + i] = ok ? sx[i] : -INFINITY;
         }
       }
@@ -264,25 +318,35 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         compute_tile(tt, kbuf, vbuf);
         tt += WPB;
       }
+      MKV_STAMP(2);
       for (; tt < t_hi; tt += WPB) {
         load_tile(tt, kbuf, vbuf);
         compute_tile(tt, kbuf, vbuf);
       }
     };
 
-    // phases: all prefill tiles plus the first decode window, then one decode window per phase;
-    // the staged logits of a window are written out by the whole work-group
+    // phases: all prefill tiles plus the first window of pool tiles, then one window per phase (the
+    // tile of appended tokens rides with the last); the staged logits of a window are written out
+    // by the whole work-group
     for (int t_lo = 0; t_lo < ntile; ++win) {
-      const int t_hi = min(ntile, ntp + (win + 1) * kWT);
+      const int t_hi = min(ntile, ntp + (win + 1) * WT);
       run_tiles(t_lo, t_hi);
-      const int wk0 = win * kSK;
-      const int nk = min(d1 - d0 - wk0, kSK);
-      if (nk > 0) {
+      const int wk0 = win * SK;
+      const int nk = min(dp - d0 - wk0, SK);
+      const bool last = t_hi == ntile;
+      if (nk > 0 || (last && nta)) {
         __syncthreads();
         for (int r = 0; r < nrows; ++r)
           for (int key = tid; key < nk; key += kThreads)
-            logit_base[(size_t)r * s.cap + d0 + wk0 + key] = sm_logit[r][key];
-        if (t_hi < ntile) {
+            logit_base[(size_t)r * s.cap + d0 + wk0 + key] = sm_logit[r * SKP + key];
+        if (last && nta) {
+          const int nn = d1 - a0;
+          for (int idx = tid; idx < nrows * nn; idx += kThreads) {
+            const int r = idx / nn, key = idx - r * nn;
+            logit_base[(size_t)r * s.cap + a0 + key] = sm_new[r][key];
+          }
+        }
+        if (!last) {
           __builtin_amdgcn_s_waitcnt(0x0F70);
           __syncthreads();
         }
@@ -290,6 +354,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       t_lo = t_hi;
     }
 
+    MKV_STAMP(3);
     // the four lanes of a row saw different keys: add up their sums (the accumulators are already
     // contracted over all keys of the wave)
     l_run += __shfl_xor(l_run, 16);
@@ -340,6 +405,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     }
     r0 += ke - ka;
   }
+  MKV_STAMP(4);
 }
 
 struct FinishMqArgs {
@@ -510,8 +576,8 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 }
 
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  // waves per work-group: variant 1 = 4, default 8
-  if (a.s.variant == 1) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
+  // waves per work-group: variant 17 = 4, default 8
+  if (a.s.variant == 17) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
   return launch_mq_w<8>(a, n_groups, occupancy, st, tm);
 }
 
@@ -530,6 +596,12 @@ hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc
   a.passes = (s.G + a.HP - 1) / a.HP;
   return launch_mq_v(a, n_groups, nullptr, st, tm);
 }
+
+#ifdef MKV_TIMELINE
+extern "C" int mkv_debug_timeline(unsigned long long* host, int n) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), (size_t)n * 8 * sizeof(unsigned long long));
+}
+#endif
 
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
   MqArgs a;
