@@ -74,12 +74,12 @@ typedef struct {
   float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
   float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
   int32_t score_mode;      /* mkv_score_mode                                                     */
-  int32_t split_keys;      /* tuning: keys per attention work-group (multiple of 64); 0 => chosen
+  int32_t split_keys;      /* tuning: keys per attention work-group (multiple of 16, >= 64); 0 => chosen
                               per step so that the launch just fills the chip                   */
-  int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default (vector-ALU
-                              kernel, or the matrix-core kernel for bf16 x 128 layers with more
-                              than four query heads per KV head); 1..15 force variants of the
-                              former, 16.. of the latter (bf16 x 128 only, else ignored)        */
+  int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default (the
+                              matrix-core kernel for bf16 x 128 layers, else the vector-ALU
+                              kernel); 1..15 force variants of the latter, 16.. of the former
+                              (bf16 x 128 only, else ignored)                                   */
   int32_t groups_per_cu;   /* tuning: attention work-groups per compute unit a launch aims for;
                               0 => library default                                              */
   int32_t max_q_len;       /* largest q_len mkv_decode_step_multi will be called with (1..16);

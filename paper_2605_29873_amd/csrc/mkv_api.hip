@@ -62,7 +62,8 @@ std::string check_config(const mkv_config* c) {
   if (!(c->alpha >= 0.0f && c->alpha <= 1.0f)) return "alpha must lie in [0, 1]";
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return "softmax_scale must be finite and >= 0";
   if (c->score_mode != MKV_SCORE_LAYER_MEAN) return "unknown score_mode";
-  if (c->split_keys < 0 || (c->split_keys % 64) != 0) return "split_keys must be a non-negative multiple of 64";
+  if (c->split_keys < 0 || (c->split_keys % 16) != 0 || (c->split_keys && c->split_keys < 64))
+    return "split_keys must be 0 or a multiple of 16 that is at least 64";
   if (c->attn_variant < 0 || c->attn_variant > 32) return "attn_variant out of range";
   if (c->groups_per_cu < 0 || c->groups_per_cu > 16) return "groups_per_cu out of range";
   if (c->max_q_len < 0 || c->max_q_len > 16) return "max_q_len must lie in [0, 16]";
@@ -90,12 +91,12 @@ Layout make_layout(const mkv_config* c) {
   L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + grow;
   L.HL = head_lanes(G);
   L.passes = (G + L.HL - 1) / L.HL;
-  // Single-query steps of bf16 x 128 layers with more than four query heads per KV head go to the
-  // matrix-core kernels too: the vector-ALU kernel spends G multiply-adds per loaded element and
-  // falls behind the memory stream there (measured on G = 7: 3.7 -> 4.9 TB/s).  attn_variant
-  // 1..15 forces the vector-ALU kernel, 16.. the matrix-core one.
+  // Single-query steps of bf16 x 128 layers run on the matrix-core kernels as well: the vector-ALU
+  // kernel spends G multiply-adds per loaded element and falls behind the memory stream as G grows
+  // (measured at G = 7: 3.7 -> 5.1 TB/s; at G = 4: 5.4 -> 5.6 TB/s).  attn_variant 1..15 forces the
+  // vector-ALU kernel, 16.. picks a variant of the matrix-core one.
   const bool mfma_ok = c->dtype == MKV_BF16 && c->head_dim == 128;
-  L.mfma_single = mfma_ok && (c->attn_variant >= 16 || (c->attn_variant == 0 && G > 4));
+  L.mfma_single = mfma_ok && (c->attn_variant == 0 || c->attn_variant >= 16);
   if (c->max_q_len > 0 || L.mfma_single) {
     const int hp = mq_heads_per_pass(G, grow);           // fewest heads per pass = most passes
     L.mq_passes = (G + hp - 1) / hp;

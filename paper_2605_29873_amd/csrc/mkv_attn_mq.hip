@@ -217,33 +217,49 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int bytes_pre = p1 * kRowB, bytes_dec = max(dp, 0) * kRowB;
     const int bytes_new = new_rows > 0 ? (new_rows - 1) * new_stride + kRowB : 0;
 
-    auto load_tile = [&](int tt, uint4 (&kr)[2][4], uint4 (&vr)[2][4]) __attribute__((always_inline)) {
+    // Loads of tile tt; a tile index at or past t_end gets an empty descriptor, i.e. zeros and no
+    // memory traffic, so that the loop below can always issue its next loads without a branch.
+    struct TileAddr { rsrc_t rk, rv; uint32_t vk, vv; int row0, stride; };
+    auto tile_addr = [&](int tt, int t_end) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
-      const int bytes = pick3(seg, bytes_pre, bytes_dec, bytes_new);
-      const rsrc_t rk = make_rsrc(pick3(seg, kpre, kdec, knew), bytes);
-      const rsrc_t rv = make_rsrc(pick3(seg, vpre, vdec, vnew), bytes);
-      const int stride = pick(seg == 2, new_stride, kRowB);
-      const int row0 = pick(seg == 2, jb - n0, jb);                   // first row of the tile in its array
-      const uint32_t vk = pick(seg == 2, vk_new, vk_pool);
-      const uint32_t vv = pick(seg == 2, vv_new, vv_pool);
+      const int bytes = tt < t_end ? pick3(seg, bytes_pre, bytes_dec, bytes_new) : 0;
+      TileAddr t;
+      t.rk = make_rsrc(pick3(seg, kpre, kdec, knew), bytes);
+      t.rv = make_rsrc(pick3(seg, vpre, vdec, vnew), bytes);
+      t.stride = pick(seg == 2, new_stride, kRowB);
+      t.row0 = pick(seg == 2, jb - n0, jb);                   // first row of the tile in its array
+      t.vk = pick(seg == 2, vk_new, vk_pool);
+      t.vv = pick(seg == 2, vv_new, vv_pool);
+      return t;
+    };
+    auto load_k = [&](int tt, int t_end, uint4 (&kr)[2][4]) __attribute__((always_inline)) {
+      const TileAddr t = tile_addr(tt, t_end);
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
-        const uint32_t so = (uint32_t)(row0 + 16 * h) * (uint32_t)stride;
+        const uint32_t so = (uint32_t)(t.row0 + 16 * h) * (uint32_t)t.stride;
 #pragma unroll
-        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = buf_load16(rk, vk + iv * 64, so);
+        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = buf_load16(t.rk, t.vk + iv * 64, so);
+      }
+    };
+    auto load_v = [&](int tt, int t_end, uint4 (&vr)[2][4]) __attribute__((always_inline)) {
+      const TileAddr t = tile_addr(tt, t_end);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vr[h][i] = buf_load16(rv, vv, so + (uint32_t)(i * stride));
+      for (int h = 0; h < 2; ++h) {
+        const uint32_t so = (uint32_t)(t.row0 + 16 * h) * (uint32_t)t.stride;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vr[h][i] = buf_load16(t.rv, t.vv, so + (uint32_t)(i * t.stride));
       }
     };
 
     int win = 0;
     constexpr float kSlack = 8.0f;
-    auto compute_tile = [&](int tt, const uint4 (&kr)[2][4], const uint4 (&vr)[2][4]) __attribute__((always_inline)) {
+    // scores of one tile against the 16 rows: x[4h + i] = logit of key 16h + 4j + i (base 2), -inf
+    // where masked; decode logits are staged for the score update
+    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], float (&x)[8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
       const int jn = pick3(seg, p1, dp, d1);
-      float x[8];
 #pragma unroll
       for (int h = 0; h < 2; ++h) {
         f32x4_t sv = {0.f, 0.f, 0.f, 0.f};
@@ -265,6 +281,9 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
           x[4 * h + i] = ok ? sx[i] : -INFINITY;
         }
       }
+    };
+    // running softmax over the tile's scores; returns the probabilities as the bf16 B operand
+    auto softmax_tile = [&](const float (&x)[8]) __attribute__((always_inline)) {
       float tm = x[0];
 #pragma unroll
       for (int i = 1; i < 8; ++i) tm = fmaxf(tm, x[i]);
@@ -287,7 +306,11 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         l_run += p;
         pb[i] = (__bf16)p;
       }
-      // V^T operand for chunk dc: element 4h + i = bf16 number dc of the vector of key 4j + i, tile h
+      return pb;
+    };
+    // acc += V^T P^T.  V^T operand for chunk dc: element 4h + i = bf16 number dc of the vector of
+    // key 4j + i, half h
+    auto value_tile = [&](const uint4 (&vr)[2][4], bf16x8_t pb) __attribute__((always_inline)) {
       uint32_t vw[2][4][4];
 #pragma unroll
       for (int h = 0; h < 2; ++h)
@@ -308,20 +331,23 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
     };
 
+    // Tiles [t_lo, t_hi), round-robin over the waves, as a two-stage pipeline on one set of
+    // registers: as soon as the scores of a tile are formed its K registers take the next tile's
+    // K, and as soon as the values are accumulated its V registers take the next tile's V, so a
+    // wave always has loads in flight.
     auto run_tiles = [&](int t_lo, int t_hi) __attribute__((always_inline)) {
       uint4 kbuf[2][4], vbuf[2][4];
       int tt = t_lo + wave;
-      const bool any = tt < t_hi;
-      if (any) load_tile(tt, kbuf, vbuf);
-      __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): no earlier store is pending inside the loop
-      if (any) {
-        compute_tile(tt, kbuf, vbuf);
+      load_k(tt, t_hi, kbuf);
+      load_v(tt, t_hi, vbuf);
+      while (tt < t_hi) {
+        float x[8];
+        score_tile(tt, kbuf, x);
+        load_k(tt + WPB, t_hi, kbuf);
+        const bf16x8_t pb = softmax_tile(x);
+        value_tile(vbuf, pb);
+        load_v(tt + WPB, t_hi, vbuf);
         tt += WPB;
-      }
-      MKV_STAMP(2);
-      for (; tt < t_hi; tt += WPB) {
-        load_tile(tt, kbuf, vbuf);
-        compute_tile(tt, kbuf, vbuf);
       }
     };
 

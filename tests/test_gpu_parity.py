@@ -236,3 +236,25 @@ def test_decode_pools_longer_than_one_logit_window(mkv, G, n_d):
         ls.load_snapshot(n_d - 1, 3 * n_d)
         _run(ls, 4, t0=3 * n_d, check_abar=True)
         assert ls.evictions == 2
+
+
+@pytest.mark.parametrize("G", [1, 2, 4, 7, 8, 12])
+def test_vector_alu_kernel_on_bf16_128_layers(mkv, G):
+    # bf16 x 128 layers default to the matrix-core kernel; attn_variant 15 keeps them on the
+    # vector-ALU kernel (the one fp32 and 64-wide layers use), which must agree as well
+    wl = X.Workload("valu", batch=2, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=128, dtype="bf16",
+                    prefill_min=50, prefill_max=333, decode_budget=20, evict_trigger=27,
+                    recent_window=3, alpha=0.65, steps=60, hh_prob=0.05)
+    ls = Lockstep(mkv, wl, split_keys=64, attn_variant=15)
+    ls.prefill()
+    _run(ls, 60, check_abar=True)
+    assert ls.evictions >= 8
+
+
+def test_cfg3_full_size_sampled_on_the_vector_alu_kernel(mkv):
+    wl = WL["cfg3"]
+    ls = Lockstep(mkv, wl, seqs=[4, 11], active=range(wl.batch), attn_variant=15)
+    ls.prefill()
+    ls.load_snapshot(wl.evict_trigger - 2, 5000)
+    _run(ls, 4, t0=5000)
+    assert ls.evictions == 2
