@@ -27,7 +27,7 @@ struct Layout {
   // per-layer regions (byte offsets inside a layer block) and the layer stride
   size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
   // scratch regions (absolute offsets), shared by all layers
-  size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, total;
+  size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, evict_key, total;
   int cap, HL, passes, max_groups;
   int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
   bool mfma_single;       // mkv_decode_step runs on the matrix-core kernels
@@ -138,6 +138,7 @@ Layout make_layout(const mkv_config* c) {
   L.lse = take(B * H * grow * 4);
   L.src_map = take(B * L.cap * 4);
   L.evict_info = take(B * 2 * 4);
+  L.evict_key = take(B * 8);
   L.total = o;
   return L;
 }
@@ -209,6 +210,7 @@ Scratch scratch_view(const mkv_ctx* c) {
   s.lse = (float*)(c->arena + c->lay.lse);
   s.src_map = (int32_t*)(c->arena + c->lay.src_map);
   s.evict_info = (int32_t*)(c->arena + c->lay.evict_info);
+  s.evict_key = (unsigned long long*)(c->arena + c->lay.evict_key);
   return s;
 }
 
@@ -245,16 +247,24 @@ int set_device_int(mkv_ctx* c, int32_t* p, int32_t v) {
 
 // Evicts the sequences of `mask` whose mirror length exceeds `threshold`; returns MKV_OK when no
 // sequence qualifies.
+// `selected`: the finishing kernel of the step just taken may have left the one-token selection
+// (single-query step with trigger == budget); it is used when every sequence that fires holds
+// exactly budget + 1 tokens.
 int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* fired = nullptr,
-              const KernelTimer* tm = nullptr) {
+              const KernelTimer* tm = nullptr, bool selected = false) {
   const int B = c->cfg.batch;
   bool any = false;
-  for (int b = 0; b < B; ++b)
-    if (mask.active(b) && c->h_nd[(size_t)layer * B + b] > threshold &&
-        c->h_nd[(size_t)layer * B + b] > c->cfg.decode_budget) any = true;
+  for (int b = 0; b < B; ++b) {
+    const int n = c->h_nd[(size_t)layer * B + b];
+    if (mask.active(b) && n > threshold && n > c->cfg.decode_budget) {
+      any = true;
+      if (n != c->cfg.decode_budget + 1) selected = false;
+    }
+  }
   if (fired) *fired = any;
   if (!any) return MKV_OK;
-  hipError_t e = launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream, tm);
+  hipError_t e = selected ? launch_evict_one(c->shape, layer_view(c, layer), scratch_view(c), mask, c->stream, tm)
+                          : launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream, tm);
   if (e != hipSuccess) return fail_hip(c, e, "evict launch");
   for (int b = 0; b < B; ++b) {
     int32_t& n = c->h_nd[(size_t)layer * B + b];
@@ -337,7 +347,8 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   int rc = MKV_OK;
   if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
     bool fired = false;
-    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr);
+    const bool selected = q_len == 1 && c->cfg.evict_trigger == c->cfg.decode_budget;
+    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr, selected);
     if (pe && fired) c->prof.evicted[c->prof.used] = 1;
   }
   if (pe) c->prof.used += 1;
@@ -390,6 +401,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   s.D = cfg->head_dim; s.bf16 = cfg->dtype == MKV_BF16;
   s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.HL = c->lay.HL; s.passes = c->lay.passes; s.max_groups = c->lay.max_groups;
   s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
+  s.trigger = cfg->evict_trigger;
   s.variant = cfg->attn_variant;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
   s.scale_log2 = (float)(scale * 1.4426950408889634074);

@@ -126,7 +126,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
     for (int b = tid; b <= s.B; b += kThreads) {
       a.sc.offs[b] = offs[b];
-      if (b < s.B && a.mask.active(b)) a.lv.nd_eff[b] = a.lv.nd[b] + 1;
+      if (b < s.B && a.mask.active(b)) {
+        a.lv.nd_eff[b] = a.lv.nd[b] + 1;
+        a.sc.evict_key[b] = ~0ull;   // the finishing kernel may leave this step's selection here
+      }
     }
   }
   const long long total = offs[s.B];
@@ -612,37 +615,45 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
     }
   }
   const int j = jb + tid;
-  if (j >= n1) return;
-  float sum0 = 0.f, sum1 = 0.f;
-  const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
-  int h = 0;
-  for (; h + 15 < s.H; h += 16) {   // sixteen independent loads in flight
-    float x[16];
+  // When the step will evict exactly one token (the paper's cadence: trigger = budget and the pool
+  // has just grown to budget + 1), the selection of Eq. 8 is an arg-min over the scores computed
+  // right here: every slot block merges its candidates' minimum into evict_key[b].
+  unsigned long long key = ~0ull;
+  if (j < n1) {
+    float sum0 = 0.f, sum1 = 0.f;
+    const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
+    int h = 0;
+    for (; h + 15 < s.H; h += 16) {   // sixteen independent loads in flight
+      float x[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) x[u] = lg[(size_t)(h + u) * s.cap];
+      for (int u = 0; u < 16; ++u) x[u] = lg[(size_t)(h + u) * s.cap];
 #pragma unroll
-    for (int u = 0; u < 16; u += 2) {
-      sum0 += fast_exp2(x[u] - smem[h + u]);
-      sum1 += fast_exp2(x[u + 1] - smem[h + u + 1]);
+      for (int u = 0; u < 16; u += 2) {
+        sum0 += fast_exp2(x[u] - smem[h + u]);
+        sum1 += fast_exp2(x[u + 1] - smem[h + u + 1]);
+      }
     }
+    for (; h + 3 < s.H; h += 4) {
+      const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
+      const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
+      sum0 += fast_exp2(x0 - smem[h]) + fast_exp2(x2 - smem[h + 2]);
+      sum1 += fast_exp2(x1 - smem[h + 1]) + fast_exp2(x3 - smem[h + 3]);
+    }
+    for (; h < s.H; ++h) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
+    const float abar = (sum0 + sum1) * a.inv_H;
+    const size_t si = (size_t)b * s.cap + j;
+    const float prev = (j == n0) ? 0.f : a.lv.score[si];
+    const float I = fmaf(s.alpha, prev, abar);
+    a.lv.score[si] = I;
+    a.sc.abar[si] = abar;
+    if (j == n0) {
+      const int t = a.lv.tpos[b];
+      a.lv.pos[si] = t;
+      a.lv.tpos[b] = t + 1;
+    }
+    if (s.trigger == s.budget && n1 == s.budget + 1 && j < n1 - s.window) key = evict_key_of(I, j);
   }
-  for (; h + 3 < s.H; h += 4) {
-    const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
-    const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
-    sum0 += fast_exp2(x0 - smem[h]) + fast_exp2(x2 - smem[h + 2]);
-    sum1 += fast_exp2(x1 - smem[h + 1]) + fast_exp2(x3 - smem[h + 3]);
-  }
-  for (; h < s.H; ++h) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
-  const float abar = (sum0 + sum1) * a.inv_H;
-  const size_t si = (size_t)b * s.cap + j;
-  const float prev = (j == n0) ? 0.f : a.lv.score[si];
-  a.lv.score[si] = fmaf(s.alpha, prev, abar);
-  a.sc.abar[si] = abar;
-  if (j == n0) {
-    const int t = a.lv.tpos[b];
-    a.lv.pos[si] = t;
-    a.lv.tpos[b] = t + 1;
-  }
+  if (s.trigger == s.budget && n1 == s.budget + 1) wave_min_key_to(key, a.sc.evict_key + b, lane);
 }
 
 // grid.x == 0 asks how many work-groups of the variant fit on one compute unit (*a.occupancy).

@@ -106,7 +106,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
       a.sc.offs[b] = offs[b];
-      if (b < s.B && a.mask.active(b)) a.lv.nd_eff[b] = a.lv.nd[b] + Q;
+      if (b < s.B && a.mask.active(b)) {
+        a.lv.nd_eff[b] = a.lv.nd[b] + Q;
+        a.sc.evict_key[b] = ~0ull;   // the finishing kernel may leave this step's selection here
+      }
     }
   }
   const long long total = uniform(offs[s.B]);
@@ -562,34 +565,42 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     }
   }
   const int j = jb + tid;
-  if (j >= n1) return;
-  const size_t si = (size_t)b * s.cap + j;
-  float I = (j < n0) ? a.lv.score[si] : 0.f;
-  float abar = 0.f;
-  // logits of row (h, qi) live at [b][h*Q + qi][slot]
-  const float* lg = a.sc.logits + (size_t)b * rows * s.cap + j;
-  for (int qi = max(0, j - n0); qi < Q; ++qi) {
-    float sum0 = 0.f, sum1 = 0.f;
-    const float* lq = lg + (size_t)qi * s.cap;
-    const float* nq = smem + qi * s.H;
-    const size_t hstride = (size_t)Q * s.cap;
-    int h = 0;
-    for (; h + 7 < s.H; h += 8) {
-      float x[8];
+  // One token appended and exactly one to evict (trigger = budget, pool at budget + 1): the
+  // selection of Eq. 8 is an arg-min over the scores computed right here; every slot block merges
+  // its candidates' minimum into evict_key[b].
+  const bool pick_one = Q == 1 && s.trigger == s.budget && n1 == s.budget + 1;
+  unsigned long long key = ~0ull;
+  if (j < n1) {
+    const size_t si = (size_t)b * s.cap + j;
+    float I = (j < n0) ? a.lv.score[si] : 0.f;
+    float abar = 0.f;
+    // logits of row (h, qi) live at [b][h*Q + qi][slot]
+    const float* lg = a.sc.logits + (size_t)b * rows * s.cap + j;
+    for (int qi = max(0, j - n0); qi < Q; ++qi) {
+      float sum0 = 0.f, sum1 = 0.f;
+      const float* lq = lg + (size_t)qi * s.cap;
+      const float* nq = smem + qi * s.H;
+      const size_t hstride = (size_t)Q * s.cap;
+      int h = 0;
+      for (; h + 7 < s.H; h += 8) {
+        float x[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) x[u] = lq[(size_t)(h + u) * hstride];
+        for (int u = 0; u < 8; ++u) x[u] = lq[(size_t)(h + u) * hstride];
 #pragma unroll
-      for (int u = 0; u < 8; u += 2) {
-        sum0 += fast_exp2(x[u] - nq[h + u]);
-        sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+        for (int u = 0; u < 8; u += 2) {
+          sum0 += fast_exp2(x[u] - nq[h + u]);
+          sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+        }
       }
+      for (; h < s.H; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
+      abar = (sum0 + sum1) * a.inv_H;
+      I = fmaf(s.alpha, I, abar);
     }
-    for (; h < s.H; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
-    abar = (sum0 + sum1) * a.inv_H;
-    I = fmaf(s.alpha, I, abar);
+    a.lv.score[si] = I;
+    a.sc.abar[si] = abar;
+    if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
   }
-  a.lv.score[si] = I;
-  a.sc.abar[si] = abar;
+  if (pick_one) wave_min_key_to(key, a.sc.evict_key + b, lane);
 }
 
 template <int WPB>

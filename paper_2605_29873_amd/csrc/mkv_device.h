@@ -139,5 +139,27 @@ __device__ __forceinline__ void wave_merge_ml(const float* ml, int stride, int n
   L = wave_sum(l_loc);
 }
 
+// Order-preserving map float -> uint32 (total order of the reals; -0 is folded onto +0 so that the
+// two zeros tie, as they do under float comparison).
+__device__ __forceinline__ uint32_t ordered_key(uint32_t bits) {
+  if (bits == 0x80000000u) bits = 0u;
+  return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+}
+
+// Selection key of a slot for Eq. 8: lowest score first, the older slot on a tie.
+__device__ __forceinline__ unsigned long long evict_key_of(float score, int slot) {
+  return ((unsigned long long)ordered_key(__builtin_bit_cast(uint32_t, score)) << 32) | (uint32_t)slot;
+}
+
+// Minimum of `key` over the wave, merged into *dst by lane 0 (~0 = no candidate).
+__device__ __forceinline__ void wave_min_key_to(unsigned long long key, unsigned long long* dst, int lane) {
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) {
+    const unsigned long long o = __shfl_xor(key, off);
+    key = o < key ? o : key;
+  }
+  if (lane == 0 && key != ~0ull) atomicMin(dst, key);
+}
+
 }  // namespace dev
 }  // namespace mkv

@@ -2,6 +2,7 @@
 // in-place compaction of K, V, scores and positions (Eq. 9), fired by the capacity check (Eq. 7).
 // Also the token-major -> head-major ingest copy used by the prefill pool.
 #include "mkv_internal.h"
+#include "mkv_device.h"
 
 #include <hip/hip_ext.h>
 
@@ -11,12 +12,7 @@ namespace {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 
-// Order-preserving map float -> uint32 (total order of the reals; -0 is folded onto +0 so that the
-// two zeros tie, as they do under float comparison).
-__device__ __forceinline__ uint32_t ordered_key(uint32_t bits) {
-  if (bits == 0x80000000u) bits = 0u;
-  return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-}
+using dev::ordered_key;
 
 __device__ __forceinline__ int wave_incl_scan(int x, int lane) {
 #pragma unroll
@@ -238,6 +234,71 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArg
   }
 }
 
+// One-token eviction with the selection already made (the paper's cadence: one token leaves per
+// step once the pool is full).  evict_key[b] holds (score key, slot) of the token that leaves, or ~0;
+// every such sequence holds n = budget + 1 tokens.  Rows, scores and positions above the slot move
+// down by one.  grid (row strips, Hkv * 2 + 1, B): y < Hkv * 2 owns a 128-byte column strip of one
+// head's K or V pool, the last y (x = 0 only) the score and position vectors.  Sources of a round
+// are read before a barrier and written after it, as in the general mover.
+__global__ __launch_bounds__(kMoveThreads) void evict_one_kernel(const EvictArgs a, int rowb) {
+  const Shape& s = a.s;
+  const int b = blockIdx.z;
+  if (!a.mask.active(b)) return;
+  const unsigned long long key = a.sc.evict_key[b];
+  if (key == ~0ull) return;
+  const int e = (int)(uint32_t)key;     // the slot that leaves
+  const int n_new = s.budget;
+  if ((int)blockIdx.y == s.Hkv * 2) {
+    if (blockIdx.x != 0) return;
+    float* score = a.lv.score + (size_t)b * s.cap;
+    int32_t* pos = a.lv.pos + (size_t)b * s.cap;
+    constexpr int kItems = kMaxDecodeCapacity / kMoveThreads;
+    float sv[kItems];
+    int32_t pv[kItems];
+#pragma unroll
+    for (int u = 0; u < kItems; ++u) {
+      const int d = e + u * kMoveThreads + (int)threadIdx.x;
+      if (d < n_new) { sv[u] = score[d + 1]; pv[u] = pos[d + 1]; }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kItems; ++u) {
+      const int d = e + u * kMoveThreads + (int)threadIdx.x;
+      if (d < n_new) { score[d] = sv[u]; pos[d] = pv[u]; }
+    }
+    if (threadIdx.x == 0) {
+      a.lv.nd[b] = n_new;
+      a.sc.evict_info[2 * b] = e;
+      a.sc.evict_info[2 * b + 1] = n_new;
+    }
+    return;
+  }
+  const int g = blockIdx.y >> 1;
+  char* pool = (char*)((blockIdx.y & 1) ? a.lv.Vd : a.lv.Kd) +
+               ((size_t)b * s.Hkv + g) * (size_t)s.dstride * rowb + blockIdx.x * kSliceBytes;
+  constexpr int kLanesPerRow = kSliceBytes / 16;
+  constexpr int kRows = kMoveThreads / kLanesPerRow;
+  constexpr int U = 8;
+  const int off = (threadIdx.x % kLanesPerRow) * 16;
+  const int r = threadIdx.x / kLanesPerRow;
+  for (int d0 = e; d0 < n_new; d0 += kRows * U) {
+    uint4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int d = d0 + u * kRows + r;
+      if (d < n_new) v[u] = *reinterpret_cast<const uint4*>(pool + (size_t)(d + 1) * rowb + off);
+    }
+    __builtin_amdgcn_s_waitcnt(0);  // every source of this round has arrived
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int d = d0 + u * kRows + r;
+      if (d < n_new) *reinterpret_cast<uint4*>(pool + (size_t)d * rowb + off) = v[u];
+    }
+  }
+}
+
 // k, v [n_tokens, Hkv, D] (token-major) -> pool rows [row0, row0 + n_tokens) of every KV head of
 // sequence `seq` (head-major).  One 16-byte vector per thread.
 __global__ void ingest_kernel(char* Kpool, char* Vpool, const char* k, const char* v, int Hkv,
@@ -281,6 +342,17 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
   const dim3 grid(rowb / kSliceBytes, s.Hkv * 2, s.B);
   if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, nullptr, tm->stop, 0, a, rowb);
   else hipLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, a, rowb);
+  return hipGetLastError();
+}
+
+hipError_t launch_evict_one(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                            hipStream_t st, const KernelTimer* tm) {
+  EvictArgs a;
+  a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = s.budget;
+  const int rowb = s.D * (s.bf16 ? 2 : 4);
+  const dim3 grid(rowb / kSliceBytes, s.Hkv * 2 + 1, s.B);
+  if (tm) hipExtLaunchKernelGGL(evict_one_kernel, grid, dim3(kMoveThreads), 0, st, tm->start, tm->stop, 0, a, rowb);
+  else hipLaunchKernelGGL(evict_one_kernel, grid, dim3(kMoveThreads), 0, st, a, rowb);
   return hipGetLastError();
 }
 

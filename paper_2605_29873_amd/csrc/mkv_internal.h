@@ -27,6 +27,7 @@ struct Shape {
   int passes;        // passes per KV head: ceil(G / HL)
   int max_groups;    // most attention work-groups a launch may use (sizes the partial buffers)
   int budget, window;
+  int trigger;       // the decode step evicts when the pool exceeds this (INT32_MAX: never)
   int variant;       // attention kernel variant (tuning), 0 = default
   float alpha;
   float scale_log2;  // softmax scale * log2(e): logits are kept in base-2 units
@@ -56,6 +57,9 @@ struct Scratch {
   float* lse;         // [B][q_len][H]     base-2 log of the softmax normaliser of the last step
   int32_t* src_map;   // [B][cap]          compaction map: new slot -> old slot
   int32_t* evict_info;  // [B][2]          (first moved slot, new pool size) of the last selection
+  // [B] when the step will evict exactly one token per sequence (trigger == budget): the finishing
+  // kernel's arg-min over (score, slot) of the candidates, ~0 if the sequence is not over budget
+  unsigned long long* evict_key;
 };
 
 // Events that bracket one kernel launch (start and stop are recorded by the launch itself).
@@ -89,6 +93,11 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
                             const KernelTimer* tm = nullptr);
+
+// One-token eviction of the sequences whose evict_key is set, all of which hold budget + 1 tokens:
+// the selection was made by the finishing kernel, this only closes the gap.
+hipError_t launch_evict_one(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                            hipStream_t st, const KernelTimer* tm = nullptr);
 
 hipError_t configure_kernels();
 

@@ -162,3 +162,55 @@ def test_caller_owned_arena(mkv):
     torch.cuda.synchronize()
     assert torch.isfinite(o).all()
     mkv.mkv_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,D,G,W", [("bf16", 128, 4, 0), ("bf16", 128, 7, 5), ("f32", 64, 2, 3), ("bf16", 64, 8, 0)])
+def test_one_token_eviction_selected_by_the_finishing_kernel(mkv, dtype, D, G, W):
+    """Paper cadence (trigger = budget): the decode step takes the arg-min inside its finishing
+    kernel and only shifts rows afterwards.  A second context runs the same steps without automatic
+    eviction and calls mkv_evict (radix/arg-min selection kernel + general mover), which the other
+    tests pin to the oracle; both must agree bit for bit after every step."""
+    from tests.harness import make_ctx, to_device
+    wl = X.Workload("one", batch=3, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=D, dtype=dtype,
+                    prefill_min=40, prefill_max=150, decode_budget=37, evict_trigger=37, recent_window=W,
+                    alpha=0.8, steps=0, hh_prob=0.05)
+    auto = make_ctx(mkv, wl, manual_evict=False)
+    manual = make_ctx(mkv, wl, manual_evict=True)
+    try:
+        mask = np.array([1, 0, 1], dtype=np.uint8)
+        for s in (0, 2):
+            k, v = X.prefill_kv(wl, 0, s)
+            dk, dv = to_device(k, dtype), to_device(v, dtype)
+            for ctx in (auto, manual):
+                mkv.mkv_prefill_append(ctx, 0, s, dk.data_ptr(), dv.data_ptr(), k.shape[0])
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        out_a = torch.zeros((3, wl.n_q_heads, D), dtype=tdt, device="cuda")
+        out_m = torch.zeros_like(out_a)
+        kvd = mkv.MKV_BF16 if dtype == "bf16" else mkv.MKV_F32
+        evictions = 0
+        for t in range(70):
+            q, k, v = X.step_batch(wl, 0, t)
+            dq, dk, dv = (to_device(x, dtype) for x in (q, k, v))
+            mkv.mkv_decode_step(auto, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out_a.data_ptr(), mask)
+            mkv.mkv_decode_step(manual, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out_m.data_ptr(), mask)
+            torch.cuda.synchronize()
+            assert torch.equal(out_a, out_m)
+            for s in (0, 2):
+                if mkv.mkv_get_lens(manual, 0, s)[1] > wl.decode_budget:
+                    mkv.mkv_evict(manual, 0, s)
+                    evictions += 1
+                sa, pa = mkv.mkv_read_scores(auto, 0, s)
+                sm, pm = mkv.mkv_read_scores(manual, 0, s)
+                assert pa.size == min(t + 1, wl.decode_budget)
+                assert np.array_equal(pa, pm), f"step {t} seq {s}: retained sets differ"
+                assert np.array_equal(sa.view(np.uint32), sm.view(np.uint32)), f"step {t} seq {s}: scores differ"
+                if t % 7 == 0 or t > 64:
+                    for g in range(wl.n_kv_heads):
+                        ka, va = mkv.mkv_read_kv(auto, 0, s, 0, g, D, kvd)
+                        km, vm = mkv.mkv_read_kv(manual, 0, s, 0, g, D, kvd)
+                        assert np.array_equal(ka, km) and np.array_equal(va, vm), f"step {t} seq {s} head {g}: rows differ"
+            assert mkv.mkv_get_lens(auto, 0, 1) == (0, 0, 0)
+        assert evictions == 2 * (70 - 37)
+    finally:
+        mkv.mkv_destroy(auto)
+        mkv.mkv_destroy(manual)
