@@ -290,9 +290,16 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   }
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
+  InlineLens lens;
+  memset(&lens, 0, sizeof lens);
+  lens.valid = B <= kInlineLens;
   int n_active = 0, max_n1 = 0;
   long long total_keys = 0;  // length of the flattened key axis of this launch
   for (int b = 0; b < B; ++b) {
+    if (lens.valid) {
+      lens.mlen[b] = c->h_mlen[(size_t)layer * B + b];
+      lens.nd[b] = c->h_nd[(size_t)layer * B + b];
+    }
     if (seq_mask && !seq_mask[b]) continue;
     const size_t i = (size_t)layer * B + b;
     if (c->h_nd[i] + q_len > c->lay.cap)
@@ -328,7 +335,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
   hipError_t e;
-  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
+  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);

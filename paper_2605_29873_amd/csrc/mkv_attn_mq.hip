@@ -38,6 +38,7 @@ struct MqArgs {
   const char* k_new;
   const char* v_new;
   SeqMask mask;
+  InlineLens lens;
   int R;        // keys per work-group
   int Q;        // query rows per sequence
   int HP;       // query heads served per pass: min(G, 16 / Q)
@@ -76,14 +77,6 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 // The V^T operand wants, per lane, one head-dim element of 8 keys: lane (r, j) loads vector r of
 // the 8 keys it contracts and transposes 16-bit halves in registers (one byte-permute per dword).
 // The accumulators then hold O[row r][8 * (4j + i) + dc] for chunk dc, i = 0..3.
-#ifdef MKV_TIMELINE
-// Tuning builds: wall-clock stamps (100 MHz) per work-group at five points of the kernel.
-__device__ unsigned long long g_timeline[8192 * 8];
-#define MKV_STAMP(i) do { if (tid == 0 && blockIdx.x < 8192) g_timeline[blockIdx.x * 8 + (i)] = wall_clock64(); } while (0)
-#else
-#define MKV_STAMP(i) do {} while (0)
-#endif
-
 template <int WPB>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   constexpr int kThreads = WPB * 64;
@@ -95,19 +88,17 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   const int j4 = lane >> 4;
   const int Q = a.Q;
   const int units = s.Hkv * a.passes;
-
-  MKV_STAMP(0);
   __shared__ long long offs[kMaxBatch + 1];
   __shared__ float sm_logit[kLogitFloats + 16 * 4];   // rows of SK + 4 floats (the pad spreads the banks)
   __shared__ float sm_new[16][kTK + 4];      // logits of the appended tokens
   __shared__ float sm_part[WPB / 2][34][64];   // a wave's accumulators, reference and sum, lane-major
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane, &a.lens);
   __syncthreads();
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
       a.sc.offs[b] = offs[b];
       if (b < s.B && a.mask.active(b)) {
-        a.lv.nd_eff[b] = a.lv.nd[b] + Q;
+        a.lv.nd_eff[b] = (a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b]) + Q;
         a.sc.evict_key[b] = ~0ull;   // the finishing kernel may leave this step's selection here
       }
     }
@@ -116,7 +107,6 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   long long r0 = (long long)blockIdx.x * a.R;
   const long long r1 = min(total, r0 + a.R);
   if (r0 >= r1) return;
-  MKV_STAMP(1);
 
   int b;
   {
@@ -132,8 +122,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     while (uniform(offs[b + 1]) <= r0) ++b;
     b = uniform(b);
     const long long ob = uniform(offs[b]);
-    const int M = uniform(a.lv.mlen[b]);
-    const int n0 = uniform(a.lv.nd[b]);
+    const int M = uniform(a.lens.valid ? a.lens.mlen[b & (kInlineLens - 1)] : a.lv.mlen[b]);
+    const int n0 = uniform(a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b]);
     const int n1 = n0 + Q;
     const int L = M + n1;
     const int ul = uniform((int)((r0 - ob) / L));   // (the 64-bit division runs on the vector ALU)
@@ -382,8 +372,6 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
       t_lo = t_hi;
     }
-
-    MKV_STAMP(3);
     // the four lanes of a row saw different keys: add up their sums (the accumulators are already
     // contracted over all keys of the wave)
     l_run += __shfl_xor(l_run, 16);
@@ -434,7 +422,6 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     }
     r0 += ke - ka;
   }
-  MKV_STAMP(4);
 }
 
 struct FinishMqArgs {
@@ -623,22 +610,16 @@ hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 int mq_heads_per_pass(int G, int q_len) { return G < 16 / q_len ? G : 16 / q_len; }
 
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
-                          const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
-                          int n_groups, hipStream_t st, const KernelTimer* tm) {
+                          const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
+                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm) {
   MqArgs a;
-  a.s = s; a.lv = lv; a.sc = sc;
+  a.s = s; a.lv = lv; a.sc = sc; a.lens = lens;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
   a.mask = mask; a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   return launch_mq_v(a, n_groups, nullptr, st, tm);
 }
-
-#ifdef MKV_TIMELINE
-extern "C" int mkv_debug_timeline(unsigned long long* host, int n) {
-  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(g_timeline), (size_t)n * 8 * sizeof(unsigned long long));
-}
-#endif
 
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
   MqArgs a;

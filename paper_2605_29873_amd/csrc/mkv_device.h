@@ -79,9 +79,24 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 // Prefix sums of the per-sequence key counts, built by one wave into LDS: offs[b] = number of keys
 // of all units of sequences < b, where a sequence has `units` = Hkv * passes units of
 // L_b = M_b + n_d + n_new keys each (0 for inactive sequences; n_new = tokens appended by the
-// step).  offs has B+1 entries.
+// step).  offs has B+1 entries.  With `il` valid the lengths come with the launch arguments.
 __device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& lv, const SeqMask& mask,
-                                              int units, int n_new, long long* offs, int lane) {
+                                              int units, int n_new, long long* offs, int lane,
+                                              const InlineLens* il = nullptr) {
+  if (il && il->valid) {   // at most 32 sequences: one per lane
+    const int b = lane;
+    long long len = 0;
+    if (b < s.B && mask.active(b)) len = (long long)units * (il->mlen[b & (kInlineLens - 1)] + il->nd[b & (kInlineLens - 1)] + n_new);
+    long long incl = len;
+#pragma unroll
+    for (int off = 1; off < kInlineLens; off <<= 1) {
+      const long long y = __shfl_up(incl, off);
+      if (lane >= off) incl += y;
+    }
+    if (b < s.B) offs[b] = incl - len;
+    if (b == s.B - 1) offs[s.B] = incl;
+    return;
+  }
   const int per = (s.B + 63) / 64;
   const int b0 = lane * per;
   long long sum = 0;

@@ -16,6 +16,15 @@ struct SeqMask {
   __host__ __device__ bool active(int b) const { return (w[b >> 6] >> (b & 63)) & 1ull; }
 };
 
+// Per-sequence lengths from the host's mirror, by value with the launch when the batch is small:
+// the kernels then start without a round trip to memory for them.
+constexpr int kInlineLens = 32;
+struct InlineLens {
+  int32_t mlen[kInlineLens];   // prefill length M
+  int32_t nd[kInlineLens];     // decode pool size before the step
+  int32_t valid;               // 0: read the lengths from LayerView instead
+};
+
 // Shapes and parameters of a context, by value to every kernel.
 struct Shape {
   int B, H, Hkv, G, D, bf16;
@@ -87,8 +96,8 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
 // A pass serves mq_heads_per_pass(G, q_len) query heads x q_len rows <= 16 rows per KV head.
 int mq_heads_per_pass(int G, int q_len);
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
-                          const void* k_new, const void* v_new, const SeqMask& mask, int keys_per_group,
-                          int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
+                          const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
+                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
