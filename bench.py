@@ -4,7 +4,8 @@
 A "step" is one pass of the whole hot path -- append, split-K attention with logit emission,
 split merge + head mean + momentum update, and (when the decode pool exceeds its trigger) selection
 and in-place compaction -- for every sequence of every layer of the workload, on synthetic inputs
-that are resident in HBM before the timed region starts.
+that are resident in HBM before the timed region starts.  bf16 layers with 128-wide heads run the
+matrix-core attention kernel (attn_mq_kernel), the others the vector-ALU one (attn_split_kernel).
 
 Prints ONE JSON line.  `value` = microseconds per decode step per layer (lower is better), with
 tokens/s and the whole-step algorithmic GB/s beside it; `roofline` covers the attention kernel,
@@ -279,6 +280,11 @@ def variant_workloads(wl):
     }
 
 
+def attn_kernel_name(wl, variant: int) -> str:
+    mfma = wl.dtype == "bf16" and wl.head_dim == 128 and (variant == 0 or variant >= 16)
+    return "attn_mq_kernel" if mfma else "attn_split_kernel"
+
+
 def measured_traffic(workload_key: str):
     """HBM bytes per attention launch from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{workload_key}_pmc.txt")
@@ -341,7 +347,7 @@ def main():
         "tokens_per_s": main_res["tokens_per_s"],
         "hbm_GBps_whole_step": main_res["step_algorithmic_GBps"],
         "hbm_frac_whole_step": main_res["step_frac_of_hbm_peak"],
-        "roofline": {"bound": "hbm", "kernel": "attn_split_kernel",
+        "roofline": {"bound": "hbm", "kernel": attn_kernel_name(wl, args.attn_variant),
                      "achieved": main_res["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": main_res["attn_GBps"] / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload),
                      "traffic_source": f"profiles/{args.workload}_pmc.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, bytes per launch)",
