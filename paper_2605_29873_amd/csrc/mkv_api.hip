@@ -312,6 +312,14 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     if (n1 > max_n1) max_n1 = n1;
   }
   if (n_active == 0) return MKV_OK;
+  if (lens.valid) {
+    long long run = 0;
+    for (int b = 0; b < B; ++b) {
+      lens.offs[b] = run;
+      if (mask.active(b)) run += (long long)c->cfg.n_kv_heads * passes * (lens.mlen[b] + lens.nd[b] + q_len);
+    }
+    lens.offs[B] = run;
+  }
   LayerView lv = layer_view(c, layer);
   Scratch sc = scratch_view(c);
   hipEvent_t* pe = nullptr;
@@ -338,7 +346,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
-  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
+  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   else e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "finish launch");
   for (int b = 0; b < B; ++b) {

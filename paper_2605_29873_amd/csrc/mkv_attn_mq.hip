@@ -430,6 +430,7 @@ struct FinishMqArgs {
   Scratch sc;
   void* out;
   SeqMask mask;
+  InlineLens lens;
   float inv_H;
   int R, Q, HP, passes;
 };
@@ -439,12 +440,12 @@ constexpr int kFinishThreads = 256;
 // Where the attention kernel left the partials of row (head h, query position qi) of sequence b:
 // first slot, number of slots, and the row's position inside a slot.
 struct RowSpan { size_t slot0; int ns; int row; };
-__device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, int b, int h, int qi, int L) {
+__device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off_b, int b, int h, int qi, int L) {
   const Shape& s = a.s;
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / a.HP;
   const int ul = g * a.passes + pass;
-  const long long off_u = a.sc.offs[b] + (long long)ul * L;
+  const long long off_u = off_b + (long long)ul * L;
   const long long kf = off_u / a.R, kl = (off_u + L - 1) / a.R;
   RowSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * a.passes + ul;
@@ -464,8 +465,12 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int b = blockIdx.y;
   if (!a.mask.active(b)) return;
   const int Q = a.Q;
-  const int M = a.lv.mlen[b];
-  const int n1 = a.lv.nd_eff[b];
+  // lengths and the sequence's start on the flattened key axis: with the launch arguments when the
+  // batch is small (no memory round trip before the first useful load), else from memory
+  const bool il = a.lens.valid;
+  const int M = il ? a.lens.mlen[b & (kInlineLens - 1)] : a.lv.mlen[b];
+  const int n1 = il ? a.lens.nd[b & (kInlineLens - 1)] + Q : a.lv.nd_eff[b];
+  const long long off_b = il ? a.lens.offs[b & (kInlineLens - 1)] : a.sc.offs[b];
   const int n0 = n1 - Q;
   const int Lb = M + n1;
   const int rows = s.H * Q;
@@ -477,17 +482,22 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     const int qi = blockIdx.x / s.H, h = blockIdx.x - qi * s.H;
     constexpr int SUB = kFinishThreads / kD;
     const int d = tid % kD, sub = tid / kD;
-    const RowSpan sp = row_span(a, b, h, qi, Lb);
+    const RowSpan sp = row_span(a, off_b, b, h, qi, Lb);
     const int ns = sp.ns;
     const float* ml = a.sc.part_ml + (sp.slot0 * 16 + sp.row) * 2;
+    const float* po = a.sc.part_o + (sp.slot0 * 16 + sp.row) * kD + d;
+    const size_t ostride = (size_t)16 * kD;
+    // a row rarely has more than a few pieces: their partial outputs are fetched alongside the
+    // (reference, sum) pairs rather than after the weights are known
+    const float pre0 = sub < ns ? po[(size_t)sub * ostride] : 0.f;
+    const float pre1 = sub + SUB < ns ? po[(size_t)(sub + SUB) * ostride] : 0.f;
     float mx, L;
     wave_merge_ml(ml, mlstride, ns, lane, mx, L);
     for (int i = tid; i < ns; i += kFinishThreads) smem[i] = fast_exp2(ml[(size_t)i * mlstride] - mx);
     __syncthreads();
-    float o0 = 0.f, o1 = 0.f;
-    const float* po = a.sc.part_o + (sp.slot0 * 16 + sp.row) * kD + d;
-    const size_t ostride = (size_t)16 * kD;
-    int i = sub;
+    float o0 = sub < ns ? smem[sub] * pre0 : 0.f;
+    float o1 = sub + SUB < ns ? smem[sub + SUB] * pre1 : 0.f;
+    int i = sub + 2 * SUB;
     for (; i + SUB < ns; i += 2 * SUB) {
       o0 = fmaf(smem[i], po[(size_t)i * ostride], o0);
       o1 = fmaf(smem[i + SUB], po[(size_t)(i + SUB) * ostride], o1);
@@ -514,6 +524,18 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
 
   const int jb = ((int)blockIdx.x - rows) * kFinishThreads;
   if (jb >= n1) return;
+  // with one query row and at most 32 heads a thread's logits fit in registers: they are fetched
+  // before the normalisers are rebuilt, so that the two memory round trips overlap
+  constexpr int kPre = 32;
+  const bool pre = Q == 1 && s.H <= kPre;
+  float xpre[kPre];
+  float prev_pre = 0.f;
+  if (pre && jb + tid < n1) {
+    const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
+#pragma unroll
+    for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
+    if (jb + tid < n0) prev_pre = a.lv.score[(size_t)b * s.cap + jb + tid];
+  }
   // normalisers of all rows, `parts` threads per row; smem: [rows], then [parts][rc]
   {
     const int rc = min(rows, kFinishThreads);
@@ -528,7 +550,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       float m_loc = -INFINITY;
       if (on) {
         const int qi = x / s.H;
-        sp = row_span(a, b, x - qi * s.H, qi, Lb);
+        sp = row_span(a, off_b, b, x - qi * s.H, qi, Lb);
         ml = a.sc.part_ml + (sp.slot0 * 16 + sp.row) * 2;
         for (int i = part; i < sp.ns; i += parts) m_loc = fmaxf(m_loc, ml[(size_t)i * mlstride]);
         red[part * rc + xx] = m_loc;
@@ -559,11 +581,21 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   unsigned long long key = ~0ull;
   if (j < n1) {
     const size_t si = (size_t)b * s.cap + j;
-    float I = (j < n0) ? a.lv.score[si] : 0.f;
+    float I = pre ? prev_pre : ((j < n0) ? a.lv.score[si] : 0.f);
     float abar = 0.f;
     // logits of row (h, qi) live at [b][h*Q + qi][slot]
     const float* lg = a.sc.logits + (size_t)b * rows * s.cap + j;
-    for (int qi = max(0, j - n0); qi < Q; ++qi) {
+    if (pre) {
+      float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+      for (int h = 0; h < kPre; h += 2) {
+        if (h < s.H) sum0 += fast_exp2(xpre[h] - smem[h]);
+        if (h + 1 < s.H) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
+      }
+      abar = (sum0 + sum1) * a.inv_H;
+      I = fmaf(s.alpha, I, abar);
+    }
+    for (int qi = pre ? Q : max(0, j - n0); qi < Q; ++qi) {
       float sum0 = 0.f, sum1 = 0.f;
       const float* lq = lg + (size_t)qi * s.cap;
       const float* nq = smem + qi * s.H;
@@ -629,10 +661,10 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
 }
 
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
-                            const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
-                            const KernelTimer* tm) {
+                            const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
+                            hipStream_t st, const KernelTimer* tm) {
   FinishMqArgs a;
-  a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.inv_H = 1.0f / (float)s.H;
+  a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.lens = lens; a.inv_H = 1.0f / (float)s.H;
   a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;

@@ -83,18 +83,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 __device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& lv, const SeqMask& mask,
                                               int units, int n_new, long long* offs, int lane,
                                               const InlineLens* il = nullptr) {
-  if (il && il->valid) {   // at most 32 sequences: one per lane
-    const int b = lane;
-    long long len = 0;
-    if (b < s.B && mask.active(b)) len = (long long)units * (il->mlen[b & (kInlineLens - 1)] + il->nd[b & (kInlineLens - 1)] + n_new);
-    long long incl = len;
-#pragma unroll
-    for (int off = 1; off < kInlineLens; off <<= 1) {
-      const long long y = __shfl_up(incl, off);
-      if (lane >= off) incl += y;
-    }
-    if (b < s.B) offs[b] = incl - len;
-    if (b == s.B - 1) offs[s.B] = incl;
+  if (il && il->valid) {   // at most 32 sequences, prefix sums made by the host
+    if (lane <= s.B) offs[lane] = il->offs[lane & (kInlineLens * 2 - 1)];
     return;
   }
   const int per = (s.B + 63) / 64;

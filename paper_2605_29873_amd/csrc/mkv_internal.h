@@ -22,6 +22,7 @@ constexpr int kInlineLens = 32;
 struct InlineLens {
   int32_t mlen[kInlineLens];   // prefill length M
   int32_t nd[kInlineLens];     // decode pool size before the step
+  long long offs[kInlineLens + 1];  // start of each sequence on the launch's flattened key axis
   int32_t valid;               // 0: read the lengths from LayerView instead
 };
 
@@ -100,8 +101,8 @@ hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc
                           int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
-                            const SeqMask& mask, int max_nd_eff, int keys_per_group, hipStream_t st,
-                            const KernelTimer* tm = nullptr);
+                            const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
+                            hipStream_t st, const KernelTimer* tm = nullptr);
 
 // One-token eviction of the sequences whose evict_key is set, all of which hold budget + 1 tokens:
 // the selection was made by the finishing kernel, this only closes the gap.
