@@ -36,8 +36,11 @@ typedef struct mkv_ctx mkv_ctx;
 typedef enum { MKV_F32 = 0, MKV_BF16 = 1 } mkv_dtype;
 
 /* MKV_SCORE_LAYER_MEAN: Eq. 4 as printed -- the mean runs over all H query heads, so there is one
- * score per decode token per (layer, sequence) and a token leaves all KV heads together. */
-typedef enum { MKV_SCORE_LAYER_MEAN = 0 } mkv_score_mode;
+ * score per decode token per (layer, sequence) and a token leaves all KV heads together.
+ * MKV_SCORE_PER_KV_HEAD: ablation of that reading -- one score vector per KV head, the mean running
+ * over the query heads of the head's group only; every KV head then keeps its own set of decode
+ * tokens (same count), chosen by its own scores. */
+typedef enum { MKV_SCORE_LAYER_MEAN = 0, MKV_SCORE_PER_KV_HEAD = 1 } mkv_score_mode;
 
 typedef enum {
   MKV_OK = 0,
@@ -173,6 +176,12 @@ int mkv_read_kv(mkv_ctx* ctx, int layer, int seq, int pool, int kv_head, void* k
  * MKV_ERR_STATE if `layer` was not the layer stepped last. */
 int mkv_read_probs(mkv_ctx* ctx, int layer, int seq, float* abar, float* lse_per_head,
                    int capacity, int* n_out);
+
+/* MKV_SCORE_PER_KV_HEAD only: selects the KV head whose score vector mkv_read_scores,
+ * mkv_write_scores and mkv_read_probs (abar) address from now on (default 0).  mkv_load_decode
+ * gives every head the same scores and positions.  MKV_ERR_ARG outside [0, n_kv_heads), and for
+ * anything but 0 in MKV_SCORE_LAYER_MEAN mode. */
+int mkv_set_score_view(mkv_ctx* ctx, int kv_head);
 
 /* Host-side bookkeeping of (layer, seq): prefill length, decode pool size, decode steps taken. */
 int mkv_get_lens(mkv_ctx* ctx, int layer, int seq, int* n_prefill, int* n_decode, int64_t* step);

@@ -15,14 +15,14 @@ _LIB = None
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmkv.so")
 
 MKV_F32, MKV_BF16 = 0, 1
-MKV_SCORE_LAYER_MEAN = 0
+MKV_SCORE_LAYER_MEAN, MKV_SCORE_PER_KV_HEAD = 0, 1
 MKV_OK, MKV_ERR_ARG, MKV_ERR_STATE, MKV_ERR_FROZEN = 0, -1, -2, -3
 MKV_ERR_CAPACITY, MKV_ERR_NOMEM, MKV_ERR_HIP = -4, -5, -6
 MKV_NEVER_EVICT = 2**31 - 1
 
 EXPORTS = ["mkv_required_bytes", "mkv_create", "mkv_destroy", "mkv_prefill_append",
            "mkv_decode_step", "mkv_decode_step_multi", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
-           "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_get_lens", "mkv_set_profiling",
+           "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_set_score_view", "mkv_get_lens", "mkv_set_profiling",
            "mkv_read_profile", "mkv_last_error"]
 
 
@@ -70,6 +70,7 @@ def load() -> C.CDLL:
     lib.mkv_load_decode.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i64]
     lib.mkv_read_kv.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, C.POINTER(i32)]
     lib.mkv_read_probs.argtypes = [vp, i32, i32, vp, vp, i32, C.POINTER(i32)]
+    lib.mkv_set_score_view.argtypes = [vp, i32]
     lib.mkv_get_lens.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
     lib.mkv_set_profiling.argtypes = [vp, i32]
     lib.mkv_read_profile.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(i64)]
@@ -183,6 +184,10 @@ def mkv_read_probs(ctx, layer, seq, n_q_heads, capacity):
     n = C.c_int()
     _check(ctx, load().mkv_read_probs(ctx, layer, seq, a.ctypes.data, lse.ctypes.data, a.size, C.byref(n)))
     return a[:n.value].copy(), lse
+
+
+def mkv_set_score_view(ctx, kv_head: int) -> None:
+    _check(ctx, load().mkv_set_score_view(ctx, kv_head))
 
 
 def mkv_set_profiling(ctx, enable: bool) -> None:

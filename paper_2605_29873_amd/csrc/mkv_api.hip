@@ -29,6 +29,7 @@ struct Layout {
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, evict_key, total;
   int cap, HL, passes, max_groups;
+  int S;                  // score vectors per sequence
   int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
   bool mfma_single;       // mkv_decode_step runs on the matrix-core kernels
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
@@ -61,7 +62,7 @@ std::string check_config(const mkv_config* c) {
     return "recent_window must lie in [0, decode_budget]";
   if (!(c->alpha >= 0.0f && c->alpha <= 1.0f)) return "alpha must lie in [0, 1]";
   if (!(c->softmax_scale >= 0.0f) || isinf(c->softmax_scale)) return "softmax_scale must be finite and >= 0";
-  if (c->score_mode != MKV_SCORE_LAYER_MEAN) return "unknown score_mode";
+  if (c->score_mode != MKV_SCORE_LAYER_MEAN && c->score_mode != MKV_SCORE_PER_KV_HEAD) return "unknown score_mode";
   if (c->split_keys < 0 || (c->split_keys % 16) != 0 || (c->split_keys && c->split_keys < 64))
     return "split_keys must be 0 or a multiple of 16 that is at least 64";
   if (c->attn_variant < 0 || c->attn_variant > 32) return "attn_variant out of range";
@@ -88,6 +89,7 @@ Layout make_layout(const mkv_config* c) {
   memset(&L, 0, sizeof L);
   const int grow = c->max_q_len > 1 ? c->max_q_len : 1;
   const int G = c->n_q_heads / c->n_kv_heads;
+  L.S = c->score_mode == MKV_SCORE_PER_KV_HEAD ? c->n_kv_heads : 1;
   L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + grow;
   L.HL = head_lanes(G);
   L.passes = (G + L.HL - 1) / L.HL;
@@ -115,8 +117,8 @@ Layout make_layout(const mkv_config* c) {
   L.Vp = take(B * Hkv * (size_t)L.pstride * D * es);
   L.Kd = take(B * Hkv * (size_t)L.dstride * D * es);
   L.Vd = take(B * Hkv * (size_t)L.dstride * D * es);
-  L.score = take(B * L.cap * 4);
-  L.pos = take(B * L.cap * 4);
+  L.score = take(B * L.S * L.cap * 4);
+  L.pos = take(B * L.S * L.cap * 4);
   L.mlen = take(B * 4);
   L.nd = take(B * 4);
   L.nd_eff = take(B * 4);
@@ -134,11 +136,11 @@ Layout make_layout(const mkv_config* c) {
   L.part_ml = take(rows * 2 * 4);
   L.offs = take((B + 1) * 8);
   L.logits = take(B * H * grow * L.cap * 4);
-  L.abar = take(B * L.cap * 4);
+  L.abar = take(B * L.S * L.cap * 4);
   L.lse = take(B * H * grow * 4);
-  L.src_map = take(B * L.cap * 4);
-  L.evict_info = take(B * 2 * 4);
-  L.evict_key = take(B * 8);
+  L.src_map = take(B * L.S * L.cap * 4);
+  L.evict_info = take(B * L.S * 2 * 4);
+  L.evict_key = take(B * L.S * 8);
   L.total = o;
   return L;
 }
@@ -169,6 +171,7 @@ struct mkv_ctx {
   std::vector<int64_t> h_step;
   std::vector<uint8_t> frozen;
   int last_layer;
+  int view;            // score vector the read/write helpers address (mkv_set_score_view)
   int last_q_len;      // query rows of the step taken last
   int target_groups;   // attention work-groups a launch aims for: compute units x groups per unit
   int mq_target_groups;  // same for the multi-query kernel
@@ -391,6 +394,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   c->stream = (hipStream_t)cfg->stream;
   c->last_layer = -1;
   c->last_q_len = 1;
+  c->view = 0;
   if (cfg->arena) {
     if (cfg->arena_bytes < c->lay.total) {
       std::string m = fmt("arena of %zu bytes given, %zu needed", cfg->arena_bytes, c->lay.total);
@@ -416,7 +420,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   s.D = cfg->head_dim; s.bf16 = cfg->dtype == MKV_BF16;
   s.max_prefill = cfg->max_prefill; s.cap = c->lay.cap; s.pstride = c->lay.pstride; s.dstride = c->lay.dstride; s.HL = c->lay.HL; s.passes = c->lay.passes; s.max_groups = c->lay.max_groups;
   s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
-  s.trigger = cfg->evict_trigger;
+  s.trigger = cfg->evict_trigger; s.S = c->lay.S;
   s.variant = cfg->attn_variant;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
   s.scale_log2 = (float)(scale * 1.4426950408889634074);
@@ -530,9 +534,9 @@ int mkv_read_scores(mkv_ctx* c, int layer, int seq, float* scores, int32_t* posi
     return fail(c, MKV_ERR_STATE, fmt("device pool size %d differs from the host mirror %d", n_dev, c->h_nd[i]));
   if (n_out) *n_out = n_dev;
   if ((scores || positions) && capacity < n_dev) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
-  if (scores && n_dev) e = hipMemcpyAsync(scores, lv.score + (size_t)seq * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
+  if (scores && n_dev) e = hipMemcpyAsync(scores, lv.score + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
   if (e == hipSuccess && positions && n_dev)
-    e = hipMemcpyAsync(positions, lv.pos + (size_t)seq * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
+    e = hipMemcpyAsync(positions, lv.pos + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, (size_t)n_dev * 4, hipMemcpyDeviceToHost, c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "read scores");
   return MKV_OK;
@@ -545,7 +549,7 @@ int mkv_write_scores(mkv_ctx* c, int layer, int seq, const float* scores, int n)
   if (n != c->h_nd[i]) return fail(c, MKV_ERR_ARG, fmt("n = %d but the pool holds %d", n, c->h_nd[i]));
   if (n == 0) return MKV_OK;
   LayerView lv = layer_view(c, layer);
-  hipError_t e = hipMemcpyAsync(lv.score + (size_t)seq * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  hipError_t e = hipMemcpyAsync(lv.score + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "write scores");
   return MKV_OK;
@@ -565,10 +569,11 @@ int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v
   const size_t i = (size_t)layer * c->cfg.batch + seq;
   LayerView lv = layer_view(c, layer);
   hipError_t e = launch_ingest(c->shape, lv.Kd, lv.Vd, c->lay.dstride, seq, 0, k, v, n, c->stream);
-  if (e == hipSuccess && n)
-    e = hipMemcpyAsync(lv.score + (size_t)seq * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
-  if (e == hipSuccess && n)
-    e = hipMemcpyAsync(lv.pos + (size_t)seq * c->lay.cap, positions, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  for (int sv = 0; sv < c->lay.S && n; ++sv) {   // every score vector starts from the same snapshot
+    const size_t vec = (size_t)seq * c->lay.S + sv;
+    if (e == hipSuccess) e = hipMemcpyAsync(lv.score + vec * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(lv.pos + vec * c->lay.cap, positions, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
+  }
   if (e != hipSuccess) return fail_hip(c, e, "load decode pool");
   int rc = set_device_int(c, lv.nd + seq, n);
   if (rc == MKV_OK) rc = set_device_int(c, lv.tpos + seq, (int32_t)next_step);
@@ -613,7 +618,7 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
   if (abar && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
   Scratch sc = scratch_view(c);
   hipError_t e = hipSuccess;
-  if (abar && n) e = hipMemcpyAsync(abar, sc.abar + (size_t)seq * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  if (abar && n) e = hipMemcpyAsync(abar, sc.abar + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
   if (e == hipSuccess && lse_per_head) {
     // [B][q_len][H]: the last query row of the sequence
     const size_t row = (size_t)seq * c->last_q_len + (c->last_q_len - 1);
@@ -623,6 +628,13 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
   if (e != hipSuccess) return fail_hip(c, e, "read probs");
   if (lse_per_head)
     for (int h = 0; h < c->cfg.n_q_heads; ++h) lse_per_head[h] *= 0.69314718055994530942f;  // base 2 -> e
+  return MKV_OK;
+}
+
+int mkv_set_score_view(mkv_ctx* c, int kv_head) {
+  if (!c) return MKV_ERR_ARG;
+  if (kv_head < 0 || kv_head >= c->lay.S) return fail(c, MKV_ERR_ARG, fmt("score vector %d outside [0, %d)", kv_head, c->lay.S));
+  c->view = kv_head;
   return MKV_OK;
 }
 

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
       a.sc.offs[b] = offs[b];
       if (b < s.B && a.mask.active(b)) {
         a.lv.nd_eff[b] = a.lv.nd[b] + 1;
-        a.sc.evict_key[b] = ~0ull;   // the finishing kernel may leave this step's selection here
+        for (int sv = 0; sv < s.S; ++sv) a.sc.evict_key[b * s.S + sv] = ~0ull;   // this step's selection may land here
       }
     }
   }
@@ -617,43 +617,48 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   const int j = jb + tid;
   // When the step will evict exactly one token (the paper's cadence: trigger = budget and the pool
   // has just grown to budget + 1), the selection of Eq. 8 is an arg-min over the scores computed
-  // right here: every slot block merges its candidates' minimum into evict_key[b].
-  unsigned long long key = ~0ull;
-  if (j < n1) {
-    float sum0 = 0.f, sum1 = 0.f;
-    const float* lg = a.sc.logits + (size_t)b * s.H * s.cap + j;
-    int h = 0;
-    for (; h + 15 < s.H; h += 16) {   // sixteen independent loads in flight
-      float x[16];
+  // right here: every slot block merges its candidates' minimum into the vector's evict_key.
+  // One score vector per sequence (mean over all H heads, Eq. 4 as printed) or one per KV head
+  // (mean over the G heads of the group): vector sv covers heads [sv*Hs, (sv+1)*Hs).
+  const int Hs = s.H / s.S;
+  const float inv_Hs = 1.0f / (float)Hs;
+  const bool pick_one = s.trigger == s.budget && n1 == s.budget + 1;
+  for (int sv = 0; sv < s.S; ++sv) {
+    unsigned long long key = ~0ull;
+    if (j < n1) {
+      float sum0 = 0.f, sum1 = 0.f;
+      const float* lg = a.sc.logits + ((size_t)b * s.H + (size_t)sv * Hs) * s.cap + j;
+      const float* nq = smem + sv * Hs;
+      int h = 0;
+      for (; h + 15 < Hs; h += 16) {   // sixteen independent loads in flight
+        float x[16];
 #pragma unroll
-      for (int u = 0; u < 16; ++u) x[u] = lg[(size_t)(h + u) * s.cap];
+        for (int u = 0; u < 16; ++u) x[u] = lg[(size_t)(h + u) * s.cap];
 #pragma unroll
-      for (int u = 0; u < 16; u += 2) {
-        sum0 += fast_exp2(x[u] - smem[h + u]);
-        sum1 += fast_exp2(x[u + 1] - smem[h + u + 1]);
+        for (int u = 0; u < 16; u += 2) {
+          sum0 += fast_exp2(x[u] - nq[h + u]);
+          sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+        }
       }
+      for (; h + 3 < Hs; h += 4) {
+        const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
+        const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
+        sum0 += fast_exp2(x0 - nq[h]) + fast_exp2(x2 - nq[h + 2]);
+        sum1 += fast_exp2(x1 - nq[h + 1]) + fast_exp2(x3 - nq[h + 3]);
+      }
+      for (; h < Hs; ++h) sum0 += fast_exp2(lg[(size_t)h * s.cap] - nq[h]);
+      const float abar = (sum0 + sum1) * inv_Hs;
+      const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
+      const float prev = (j == n0) ? 0.f : a.lv.score[si];
+      const float I = fmaf(s.alpha, prev, abar);
+      a.lv.score[si] = I;
+      a.sc.abar[si] = abar;
+      if (j == n0) a.lv.pos[si] = a.lv.tpos[b];
+      if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
     }
-    for (; h + 3 < s.H; h += 4) {
-      const float x0 = lg[(size_t)h * s.cap], x1 = lg[(size_t)(h + 1) * s.cap];
-      const float x2 = lg[(size_t)(h + 2) * s.cap], x3 = lg[(size_t)(h + 3) * s.cap];
-      sum0 += fast_exp2(x0 - smem[h]) + fast_exp2(x2 - smem[h + 2]);
-      sum1 += fast_exp2(x1 - smem[h + 1]) + fast_exp2(x3 - smem[h + 3]);
-    }
-    for (; h < s.H; ++h) sum0 += fast_exp2(lg[(size_t)h * s.cap] - smem[h]);
-    const float abar = (sum0 + sum1) * a.inv_H;
-    const size_t si = (size_t)b * s.cap + j;
-    const float prev = (j == n0) ? 0.f : a.lv.score[si];
-    const float I = fmaf(s.alpha, prev, abar);
-    a.lv.score[si] = I;
-    a.sc.abar[si] = abar;
-    if (j == n0) {
-      const int t = a.lv.tpos[b];
-      a.lv.pos[si] = t;
-      a.lv.tpos[b] = t + 1;
-    }
-    if (s.trigger == s.budget && n1 == s.budget + 1 && j < n1 - s.window) key = evict_key_of(I, j);
+    if (pick_one) wave_min_key_to(key, a.sc.evict_key + b * s.S + sv, lane);
   }
-  if (s.trigger == s.budget && n1 == s.budget + 1) wave_min_key_to(key, a.sc.evict_key + b, lane);
+  if (j == n0) a.lv.tpos[b] += 1;
 }
 
 // grid.x == 0 asks how many work-groups of the variant fit on one compute unit (*a.occupancy).

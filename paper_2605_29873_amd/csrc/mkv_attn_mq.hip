@@ -99,7 +99,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       a.sc.offs[b] = offs[b];
       if (b < s.B && a.mask.active(b)) {
         a.lv.nd_eff[b] = (a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b]) + Q;
-        a.sc.evict_key[b] = ~0ull;   // the finishing kernel may leave this step's selection here
+        for (int sv = 0; sv < s.S; ++sv) a.sc.evict_key[b * s.S + sv] = ~0ull;   // this step's selection may land here
       }
     }
   }
@@ -168,10 +168,11 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         char* dst = (char*)(vsel ? a.lv.Vd : a.lv.Kd) + (head_row * (size_t)s.dstride + (size_t)jn) * kRowB + vec * 16;
         *reinterpret_cast<uint4*>(dst) = ldg16(src);
       }
-      if (g == 0) {
+      if (g == 0 || s.S > 1) {     // positions: one vector per sequence, or one per KV head
         const int t0 = a.lv.tpos[b];
+        const size_t vec = (size_t)b * s.S + (s.S > 1 ? g : 0);
         for (int idx = tid; idx < d1 - a0; idx += kThreads)
-          a.lv.pos[(size_t)b * s.cap + a0 + idx] = t0 + (a0 + idx - n0);
+          a.lv.pos[vec * s.cap + a0 + idx] = t0 + (a0 + idx - n0);
       }
     }
 
@@ -529,12 +530,10 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   constexpr int kPre = 32;
   const bool pre = Q == 1 && s.H <= kPre;
   float xpre[kPre];
-  float prev_pre = 0.f;
   if (pre && jb + tid < n1) {
     const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
 #pragma unroll
     for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
-    if (jb + tid < n0) prev_pre = a.lv.score[(size_t)b * s.cap + jb + tid];
   }
   // normalisers of all rows, `parts` threads per row; smem: [rows], then [parts][rc]
   {
@@ -576,50 +575,57 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int j = jb + tid;
   // One token appended and exactly one to evict (trigger = budget, pool at budget + 1): the
   // selection of Eq. 8 is an arg-min over the scores computed right here; every slot block merges
-  // its candidates' minimum into evict_key[b].
+  // its candidates' minimum into the vector's evict_key.
   const bool pick_one = Q == 1 && s.trigger == s.budget && n1 == s.budget + 1;
-  unsigned long long key = ~0ull;
-  if (j < n1) {
-    const size_t si = (size_t)b * s.cap + j;
-    float I = pre ? prev_pre : ((j < n0) ? a.lv.score[si] : 0.f);
-    float abar = 0.f;
-    // logits of row (h, qi) live at [b][h*Q + qi][slot]
-    const float* lg = a.sc.logits + (size_t)b * rows * s.cap + j;
-    if (pre) {
-      float sum0 = 0.f, sum1 = 0.f;
+  // One score vector per sequence (mean over all H heads, Eq. 4 as printed) or one per KV head
+  // (mean over the G heads of the group): vector sv covers heads [sv*Hs, (sv+1)*Hs).
+  const int Hs = s.H / s.S;
+  const float inv_Hs = 1.0f / (float)Hs;
+  for (int sv = 0; sv < s.S; ++sv) {
+    unsigned long long key = ~0ull;
+    if (j < n1) {
+      const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
+      float I = (j < n0) ? a.lv.score[si] : 0.f;
+      float abar = 0.f;
+      if (pre) {
+        float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
-      for (int h = 0; h < kPre; h += 2) {
-        if (h < s.H) sum0 += fast_exp2(xpre[h] - smem[h]);
-        if (h + 1 < s.H) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
-      }
-      abar = (sum0 + sum1) * a.inv_H;
-      I = fmaf(s.alpha, I, abar);
-    }
-    for (int qi = pre ? Q : max(0, j - n0); qi < Q; ++qi) {
-      float sum0 = 0.f, sum1 = 0.f;
-      const float* lq = lg + (size_t)qi * s.cap;
-      const float* nq = smem + qi * s.H;
-      const size_t hstride = (size_t)Q * s.cap;
-      int h = 0;
-      for (; h + 7 < s.H; h += 8) {
-        float x[8];
+        for (int h = 0; h < kPre; h += 2) {
+          if (h >= sv * Hs && h < (sv + 1) * Hs) sum0 += fast_exp2(xpre[h] - smem[h]);
+          if (h + 1 >= sv * Hs && h + 1 < (sv + 1) * Hs) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
+        }
+        abar = (sum0 + sum1) * inv_Hs;
+        I = fmaf(s.alpha, I, abar);
+      } else {
+        // logits of row (h, qi) live at [b][h*Q + qi][slot]
+        const float* lg = a.sc.logits + ((size_t)b * rows + (size_t)sv * Hs * Q) * s.cap + j;
+        for (int qi = max(0, j - n0); qi < Q; ++qi) {
+          float sum0 = 0.f, sum1 = 0.f;
+          const float* lq = lg + (size_t)qi * s.cap;
+          const float* nq = smem + qi * s.H + sv * Hs;
+          const size_t hstride = (size_t)Q * s.cap;
+          int h = 0;
+          for (; h + 7 < Hs; h += 8) {
+            float x[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = lq[(size_t)(h + u) * hstride];
+            for (int u = 0; u < 8; ++u) x[u] = lq[(size_t)(h + u) * hstride];
 #pragma unroll
-        for (int u = 0; u < 8; u += 2) {
-          sum0 += fast_exp2(x[u] - nq[h + u]);
-          sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+            for (int u = 0; u < 8; u += 2) {
+              sum0 += fast_exp2(x[u] - nq[h + u]);
+              sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+            }
+          }
+          for (; h < Hs; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
+          abar = (sum0 + sum1) * inv_Hs;
+          I = fmaf(s.alpha, I, abar);
         }
       }
-      for (; h < s.H; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
-      abar = (sum0 + sum1) * a.inv_H;
-      I = fmaf(s.alpha, I, abar);
+      a.lv.score[si] = I;
+      a.sc.abar[si] = abar;
+      if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
     }
-    a.lv.score[si] = I;
-    a.sc.abar[si] = abar;
-    if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+    if (pick_one) wave_min_key_to(key, a.sc.evict_key + b * s.S + sv, lane);
   }
-  if (pick_one) wave_min_key_to(key, a.sc.evict_key + b, lane);
 }
 
 template <int WPB>

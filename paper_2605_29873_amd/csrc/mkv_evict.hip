@@ -49,7 +49,7 @@ struct EvictArgs {
   int threshold;
 };
 
-// One work-group per sequence.  The pool's scores and positions sit in LDS; a 4-pass, 8-bit
+// One work-group per score vector (one per sequence, or one per KV head).  The pool's scores and positions sit in LDS; a 4-pass, 8-bit
 // most-significant-first radix select finds the value of the overflow-th smallest candidate score;
 // candidates below it leave, and of those equal to it the oldest (lowest slot = smallest position,
 // because compaction is stable) leave until the count is met.  A prefix sum over the keep flags
@@ -57,11 +57,12 @@ struct EvictArgs {
 // new-slot -> old-slot map is left for the row mover.
 __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictArgs a) {
   const Shape& s = a.s;
-  const int b = blockIdx.x;
+  const int vec = blockIdx.x;          // score vector: (sequence, vector of the sequence)
+  const int b = vec / s.S;
   if (!a.mask.active(b)) return;
   const int tid = threadIdx.x;
   const int n = a.lv.nd[b];
-  int* info = a.sc.evict_info + 2 * b;
+  int* info = a.sc.evict_info + 2 * vec;
   if (n <= a.threshold || n <= s.budget) {  // Eq. 7: overflow = 0, nothing to do
     if (tid == 0) { info[0] = n; info[1] = n; }
     return;
@@ -77,8 +78,8 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
   __shared__ int sh_krem, sh_first;
   __shared__ int wave_sums[kSelWaves];
 
-  float* score = a.lv.score + (size_t)b * s.cap;
-  int32_t* pos = a.lv.pos + (size_t)b * s.cap;
+  float* score = a.lv.score + (size_t)vec * s.cap;
+  int32_t* pos = a.lv.pos + (size_t)vec * s.cap;
   for (int j = tid; j < n; j += kSelThreads) {
     raw[j] = __builtin_bit_cast(uint32_t, score[j]);
     posl[j] = pos[j];
@@ -106,7 +107,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
 #pragma unroll
     for (int w = 1; w < kSelWaves; ++w) best = wave_best[w] < best ? wave_best[w] : best;
     const int e = (int)(uint32_t)best;          // the evicted slot; survivors above it move down by one
-    int32_t* map1 = a.sc.src_map + (size_t)b * s.cap;
+    int32_t* map1 = a.sc.src_map + (size_t)vec * s.cap;
     for (int j = e + 1 + tid; j < n; j += kSelThreads) {
       map1[j - 1] = j;
       score[j - 1] = __builtin_bit_cast(float, raw[j]);
@@ -114,8 +115,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
     }
     if (tid == 0) {
       info[0] = e;
-      info[1] = n - 1;
-      a.lv.nd[b] = n - 1;
+      info[1] = n - 1;   // the row mover publishes the new pool size (other vectors still read nd)
     }
     return;
   }
@@ -174,7 +174,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
   }
   int dst = block_excl_scan(keep_cnt, wave_sums, &total);
   int first = n;
-  int32_t* map = a.sc.src_map + (size_t)b * s.cap;
+  int32_t* map = a.sc.src_map + (size_t)vec * s.cap;
   for (int j = jb; j < je; ++j) {
     if ((evict_bits >> (j - jb)) & 1ull) { first = min(first, j); continue; }
     map[dst] = j;
@@ -186,8 +186,7 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
   __syncthreads();
   if (tid == 0) {
     info[0] = sh_first;   // slots below the first hole stay where they are
-    info[1] = total;      // = budget
-    a.lv.nd[b] = total;
+    info[1] = total;      // = budget; published as the pool size by the row mover
   }
 }
 
@@ -206,13 +205,15 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArg
   const Shape& s = a.s;
   const int b = blockIdx.z;
   if (!a.mask.active(b)) return;
-  const int* info = a.sc.evict_info + 2 * b;
-  const int first = info[0], n_new = info[1];
-  if (first >= n_new) return;
   const int g = blockIdx.y >> 1;
+  const int vec = b * s.S + (s.S > 1 ? g : 0);   // the score vector that governs this KV head
+  const int* info = a.sc.evict_info + 2 * vec;
+  const int first = info[0], n_new = info[1];
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) a.lv.nd[b] = n_new;
+  if (first >= n_new) return;
   char* pool = (char*)((blockIdx.y & 1) ? a.lv.Vd : a.lv.Kd) +
                ((size_t)b * s.Hkv + g) * (size_t)s.dstride * rowb + blockIdx.x * kSliceBytes;
-  const int32_t* map = a.sc.src_map + (size_t)b * s.cap;
+  const int32_t* map = a.sc.src_map + (size_t)vec * s.cap;
   constexpr int kLanesPerRow = kSliceBytes / 16;
   constexpr int kRows = kMoveThreads / kLanesPerRow;
   const int off = (threadIdx.x % kLanesPerRow) * 16;
@@ -237,21 +238,25 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArg
 // One-token eviction with the selection already made (the paper's cadence: one token leaves per
 // step once the pool is full).  evict_key[b] holds (score key, slot) of the token that leaves, or ~0;
 // every such sequence holds n = budget + 1 tokens.  Rows, scores and positions above the slot move
-// down by one.  grid (row strips, Hkv * 2 + 1, B): y < Hkv * 2 owns a 128-byte column strip of one
-// head's K or V pool, the last y (x = 0 only) the score and position vectors.  Sources of a round
+// down by one.  grid (row strips, Hkv * 2 + S, B): y < Hkv * 2 owns a 128-byte column strip of one
+// head's K or V pool, the last S values of y (x = 0 only) a score and position vector each.  Sources of a round
 // are read before a barrier and written after it, as in the general mover.
 __global__ __launch_bounds__(kMoveThreads) void evict_one_kernel(const EvictArgs a, int rowb) {
   const Shape& s = a.s;
   const int b = blockIdx.z;
   if (!a.mask.active(b)) return;
-  const unsigned long long key = a.sc.evict_key[b];
+  const bool rows_part = (int)blockIdx.y < s.Hkv * 2;
+  const int g = blockIdx.y >> 1;
+  // score vector: the one that governs this KV head, or the one whose scores this block shifts
+  const int vec = b * s.S + (rows_part ? (s.S > 1 ? g : 0) : (int)blockIdx.y - s.Hkv * 2);
+  const unsigned long long key = a.sc.evict_key[vec];
   if (key == ~0ull) return;
   const int e = (int)(uint32_t)key;     // the slot that leaves
   const int n_new = s.budget;
-  if ((int)blockIdx.y == s.Hkv * 2) {
+  if (!rows_part) {
     if (blockIdx.x != 0) return;
-    float* score = a.lv.score + (size_t)b * s.cap;
-    int32_t* pos = a.lv.pos + (size_t)b * s.cap;
+    float* score = a.lv.score + (size_t)vec * s.cap;
+    int32_t* pos = a.lv.pos + (size_t)vec * s.cap;
     constexpr int kItems = kMaxDecodeCapacity / kMoveThreads;
     float sv[kItems];
     int32_t pv[kItems];
@@ -269,12 +274,11 @@ __global__ __launch_bounds__(kMoveThreads) void evict_one_kernel(const EvictArgs
     }
     if (threadIdx.x == 0) {
       a.lv.nd[b] = n_new;
-      a.sc.evict_info[2 * b] = e;
-      a.sc.evict_info[2 * b + 1] = n_new;
+      a.sc.evict_info[2 * vec] = e;
+      a.sc.evict_info[2 * vec + 1] = n_new;
     }
     return;
   }
-  const int g = blockIdx.y >> 1;
   char* pool = (char*)((blockIdx.y & 1) ? a.lv.Vd : a.lv.Kd) +
                ((size_t)b * s.Hkv + g) * (size_t)s.dstride * rowb + blockIdx.x * kSliceBytes;
   constexpr int kLanesPerRow = kSliceBytes / 16;
@@ -332,8 +336,8 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
   a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = threshold;
   const size_t smem = (size_t)s.cap * 8;
   // with a timer: start is taken at the selection kernel, stop after the row mover
-  if (tm) hipExtLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, tm->start, nullptr, 0, a);
-  else hipLaunchKernelGGL(evict_select_kernel, dim3(s.B), dim3(kSelThreads), smem, st, a);
+  if (tm) hipExtLaunchKernelGGL(evict_select_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, tm->start, nullptr, 0, a);
+  else hipLaunchKernelGGL(evict_select_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rowb = s.D * (s.bf16 ? 2 : 4);
@@ -350,7 +354,7 @@ hipError_t launch_evict_one(const Shape& s, const LayerView& lv, const Scratch& 
   EvictArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = s.budget;
   const int rowb = s.D * (s.bf16 ? 2 : 4);
-  const dim3 grid(rowb / kSliceBytes, s.Hkv * 2 + 1, s.B);
+  const dim3 grid(rowb / kSliceBytes, s.Hkv * 2 + s.S, s.B);
   if (tm) hipExtLaunchKernelGGL(evict_one_kernel, grid, dim3(kMoveThreads), 0, st, tm->start, tm->stop, 0, a, rowb);
   else hipLaunchKernelGGL(evict_one_kernel, grid, dim3(kMoveThreads), 0, st, a, rowb);
   return hipGetLastError();

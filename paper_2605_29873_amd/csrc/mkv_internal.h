@@ -36,6 +36,7 @@ struct Shape {
   int HL;            // query heads one attention pass serves per KV head: 1, 2, 4 or 8
   int passes;        // passes per KV head: ceil(G / HL)
   int max_groups;    // most attention work-groups a launch may use (sizes the partial buffers)
+  int S;             // score vectors per sequence: 1 (mean over all query heads) or Hkv (one per KV head)
   int budget, window;
   int trigger;       // the decode step evicts when the pool exceeds this (INT32_MAX: never)
   int variant;       // attention kernel variant (tuning), 0 = default
@@ -47,8 +48,9 @@ struct Shape {
 struct LayerView {
   void* Kp; void* Vp;      // prefill pool
   void* Kd; void* Vd;      // decode pool
-  float* score;            // [B][cap]   importance vector I
-  int32_t* pos;            // [B][cap]   original decode position of each slot
+  float* score;            // [B][S][cap]   importance vector(s) I
+  int32_t* pos;            // [B][S][cap]   original decode position of each slot (per vector: with
+                           //               S = Hkv the KV heads retain different tokens)
   int32_t* mlen;           // [B]        prefill length M
   int32_t* nd;             // [B]        decode pool size before the step in flight
   int32_t* nd_eff;         // [B]        decode pool size including the token appended in this step
@@ -63,11 +65,11 @@ struct Scratch {
   float* part_ml;     // [max_groups + B*Hkv*passes][HL][2]
   long long* offs;    // [B+1]  prefix sums of the per-sequence key counts of the last launch
   float* logits;      // [B][H*q_len][cap] base-2 logits of decode keys (q_len = 1 in the single-query step)
-  float* abar;        // [B][cap]          head-mean decode-slice attention of the last step
+  float* abar;        // [B][S][cap]       head-mean decode-slice attention of the last step
   float* lse;         // [B][q_len][H]     base-2 log of the softmax normaliser of the last step
-  int32_t* src_map;   // [B][cap]          compaction map: new slot -> old slot
-  int32_t* evict_info;  // [B][2]          (first moved slot, new pool size) of the last selection
-  // [B] when the step will evict exactly one token per sequence (trigger == budget): the finishing
+  int32_t* src_map;   // [B][S][cap]       compaction map: new slot -> old slot
+  int32_t* evict_info;  // [B][S][2]       (first moved slot, new pool size) of the last selection
+  // [B][S] when the step will evict exactly one token per sequence (trigger == budget): the finishing
   // kernel's arg-min over (score, slot) of the candidates, ~0 if the sequence is not over budget
   unsigned long long* evict_key;
 };

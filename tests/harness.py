@@ -31,7 +31,7 @@ def from_device(t: torch.Tensor) -> np.ndarray:
 
 def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = None,
              split_keys: int = 0, max_prefill: int | None = None, stream: int | None = None,
-             max_q_len: int = 0, attn_variant: int = 0):
+             max_q_len: int = 0, attn_variant: int = 0, score_mode: int = 0):
     cfg = mkv.make_config(
         n_layers=wl.n_layers if layers is None else layers, batch=wl.batch,
         n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
@@ -40,7 +40,7 @@ def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = No
         decode_budget=wl.decode_budget,
         evict_trigger=mkv.MKV_NEVER_EVICT if manual_evict else wl.evict_trigger,
         decode_capacity=wl.capacity + max(0, max_q_len - 1), recent_window=wl.recent_window,
-        alpha=wl.alpha, softmax_scale=0.0, score_mode=mkv.MKV_SCORE_LAYER_MEAN,
+        alpha=wl.alpha, softmax_scale=0.0, score_mode=score_mode,
         split_keys=split_keys, max_q_len=max_q_len, attn_variant=attn_variant,
         stream=stream if stream is not None else torch.cuda.current_stream().cuda_stream)
     return mkv.mkv_create(cfg)
