@@ -111,6 +111,16 @@ int mkv_destroy(mkv_ctx* ctx);
  * "is retained in full and never evicted").  MKV_ERR_CAPACITY beyond max_prefill. */
 int mkv_prefill_append(mkv_ctx* ctx, int layer, int seq, const void* k, const void* v, int n_tokens);
 
+/* Prompt compression before decoding starts ("Integration of Moment-KV with Prefill Compression
+ * Techniques": a prefill-phase method keeps a budget of prompt tokens, Moment-KV then manages the
+ * decode pool).  token_scores: device pointer, float[n_prefill], the prefill method's importance
+ * of every prompt token of (layer, seq) -- computing it is that method's business.  The `keep`
+ * highest-scoring tokens stay, in prompt order (lowest scores leave first, the earlier token on a
+ * tie), for all KV heads alike; the pool is compacted in place and its length becomes `keep`.
+ * No effect if keep >= n_prefill.  MKV_ERR_FROZEN after the sequence's first decode step,
+ * MKV_ERR_CAPACITY if max_prefill exceeds 16384 (the selection keeps one pool in on-chip memory). */
+int mkv_prefill_compress(mkv_ctx* ctx, int layer, int seq, const float* token_scores, int keep);
+
 /* One pass of Algorithm 1 for every active sequence of one layer.
  *   q     device pointer [batch, n_q_heads, head_dim]   the step's queries
  *   k_new device pointer [batch, n_kv_heads, head_dim]  appended to the decode pool with I = 0

@@ -28,6 +28,7 @@ struct Layout {
   size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, evict_key, total;
+  size_t p_score, p_pos, p_map, p_info;   // prompt compression: one sequence at a time
   int cap, HL, passes, max_groups;
   int S;                  // score vectors per sequence
   int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
@@ -141,11 +142,21 @@ Layout make_layout(const mkv_config* c) {
   L.src_map = take(B * L.S * L.cap * 4);
   L.evict_info = take(B * L.S * 2 * 4);
   L.evict_key = take(B * L.S * 8);
+  if (c->max_prefill > 0 && c->max_prefill <= kMaxDecodeCapacity) {
+    L.p_score = take((size_t)c->max_prefill * 4);
+    L.p_pos = take((size_t)c->max_prefill * 4);
+    L.p_map = take((size_t)c->max_prefill * 4);
+    L.p_info = take(4 * 4);      // (first moved slot, new size), then the row count the kernels read
+  }
   L.total = o;
   return L;
 }
 
 __global__ void set_int_kernel(int32_t* p, int32_t v) { *p = v; }
+__global__ void iota_kernel(int32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = i;
+}
 
 }  // namespace
 
@@ -492,6 +503,52 @@ int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void
   int rc = set_device_int(c, lv.mlen + seq, c->h_mlen[i] + n_tokens);
   if (rc != MKV_OK) return rc;
   c->h_mlen[i] += n_tokens;
+  return MKV_OK;
+}
+
+int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scores, int keep) {
+  if (!c) return MKV_ERR_ARG;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  if (!token_scores || keep < 1) return fail(c, MKV_ERR_ARG, "token_scores NULL or keep < 1");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  if (c->frozen[i]) return fail(c, MKV_ERR_FROZEN, "prefill pool is frozen after the first decode step");
+  const int M = c->h_mlen[i];
+  if (keep >= M) return MKV_OK;
+  if (c->cfg.max_prefill > kMaxDecodeCapacity)
+    return fail(c, MKV_ERR_CAPACITY, fmt("prompt compression handles pools of up to %d tokens (max_prefill is %d)",
+                                         kMaxDecodeCapacity, c->cfg.max_prefill));
+  // The selection and compaction kernels of the decode pool, pointed at this sequence's prefill
+  // pool: one sequence, one score vector, budget = keep, no protected window.
+  Shape s = c->shape;
+  s.B = 1; s.S = 1; s.cap = c->cfg.max_prefill; s.dstride = c->lay.pstride;
+  s.budget = keep; s.window = 0; s.trigger = MKV_NEVER_EVICT;
+  LayerView lv = layer_view(c, layer);
+  const size_t rowb = (size_t)c->cfg.head_dim * (c->cfg.dtype == MKV_BF16 ? 2 : 4);
+  const size_t seq_off = (size_t)seq * c->cfg.n_kv_heads * c->lay.pstride * rowb;
+  int32_t* info = (int32_t*)(c->arena + c->lay.p_info);
+  LayerView pv = lv;
+  pv.Kd = (char*)lv.Kp + seq_off; pv.Vd = (char*)lv.Vp + seq_off;
+  pv.score = (float*)(c->arena + c->lay.p_score);
+  pv.pos = (int32_t*)(c->arena + c->lay.p_pos);
+  pv.nd = info + 2;
+  Scratch sc = scratch_view(c);
+  sc.src_map = (int32_t*)(c->arena + c->lay.p_map);
+  sc.evict_info = info;
+  hipError_t e = hipMemcpyAsync(pv.score, token_scores, (size_t)M * 4, hipMemcpyDeviceToDevice, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "copy of the token scores");
+  hipLaunchKernelGGL(iota_kernel, dim3((M + 255) / 256), dim3(256), 0, c->stream, pv.pos, M);
+  e = hipGetLastError();
+  if (e != hipSuccess) return fail_hip(c, e, "iota launch");
+  int rc = set_device_int(c, pv.nd, M);
+  if (rc != MKV_OK) return rc;
+  SeqMask mask;
+  memset(&mask, 0, sizeof mask);
+  mask.w[0] = 1ull;
+  e = launch_evict(s, pv, sc, mask, keep, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "prompt compression launch");
+  rc = set_device_int(c, lv.mlen + seq, keep);
+  if (rc != MKV_OK) return rc;
+  c->h_mlen[i] = keep;
   return MKV_OK;
 }
 
