@@ -42,6 +42,9 @@ def parse_args():
     ap.add_argument("--q-len", type=int, default=0,
                     help="tokens per sequence and call: 0 = mkv_decode_step (the headline path); N >= 1 = "
                          "mkv_decode_step_multi with N query rows (matrix-core kernel), reported under 'multi_query'")
+    ap.add_argument("--producer-hidden", type=int, default=0,
+                    help="also time the step with the fused k/v producer (mkv_project_append, hidden size N) in "
+                         "front of it, reported under 'producer'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--variants", action="store_true",
                     help="also time score-rule variants of the main workload (same kernels, other parameters)")
@@ -237,6 +240,53 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0):
         job.close()
 
 
+def measure_producer(wl, hidden, steps, warmup):
+    """The decode step fed by mkv_project_append (k/v projection + rotary encoding written into the
+    pool) against the same step fed with ready-made k_new / v_new."""
+    job = Job(wl)
+    try:
+        torch, mkv = job.torch, job.mkv
+        n = wl.n_kv_heads * wl.head_dim
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(wl.seed + 1)
+        draw = lambda *shape: torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32)
+        wk = (draw(n, hidden) / hidden ** 0.5).to(torch.bfloat16)
+        wv = (draw(n, hidden) / hidden ** 0.5).to(torch.bfloat16)
+        xs = draw(job.BANK, wl.batch, hidden).to(torch.bfloat16)
+        pos = torch.tensor([job.lens[s] + 4 * wl.capacity for s in range(wl.batch)], dtype=torch.int32, device="cuda")
+        out_ptr = job.out.data_ptr()
+
+        def run(n_steps, fused):
+            for _ in range(n_steps):
+                i = job.t % job.BANK
+                if fused:
+                    mkv.mkv_project_append(job.ctx, 0, xs[i].data_ptr(), wk.data_ptr(), wv.data_ptr(), hidden,
+                                           pos.data_ptr(), 500000.0)
+                    mkv.mkv_decode_step(job.ctx, 0, job.q[0][i].data_ptr(), None, None, out_ptr)
+                else:
+                    mkv.mkv_decode_step(job.ctx, 0, job.q[0][i].data_ptr(), job.k[0][i].data_ptr(),
+                                        job.v[0][i].data_ptr(), out_ptr)
+                job.t += 1
+        res = {}
+        for fused in (False, True):
+            run(warmup, fused)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            run(steps, fused)
+            e1.record()
+            torch.cuda.synchronize()
+            res["fused_us_per_step" if fused else "plain_us_per_step"] = e0.elapsed_time(e1) * 1e3 / steps
+        wbytes = 2 * n * hidden * 2
+        res.update({"hidden": hidden, "weight_bytes": wbytes,
+                    "producer_us": res["fused_us_per_step"] - res["plain_us_per_step"],
+                    "note": "layer 0 only; producer_us = fused step - plain step (two launches: partial products, rotate+store)"})
+        res["producer_weight_GBps"] = wbytes / (res["producer_us"] * 1e-6) / 1e9
+        return res
+    finally:
+        job.close()
+
+
 def cpu_baseline(wl, seconds):
     """The oracle as it stands, one sequence of the workload from a budget-full pool, timed for
     about `seconds`; scaled to the whole batch (sequences are independent)."""
@@ -362,6 +412,8 @@ def main():
         r["q_len"] = args.q_len
         r["note"] = "one call = q_len tokens per sequence; us_per_step_per_layer is per call"
         line["multi_query"] = r
+    if args.producer_hidden:
+        line["producer"] = measure_producer(wl, args.producer_hidden, min(args.steps, 128), 16)
     if args.variants:
         line["variants"] = {}
         for name, w in variant_workloads(wl).items():

@@ -121,10 +121,31 @@ int mkv_prefill_append(mkv_ctx* ctx, int layer, int seq, const void* k, const vo
  * MKV_ERR_CAPACITY if max_prefill exceeds 16384 (the selection keeps one pool in on-chip memory). */
 int mkv_prefill_compress(mkv_ctx* ctx, int layer, int seq, const float* token_scores, int keep);
 
+/* The producer of the token that the next decode step appends (Algorithm 1, "ComputeQKV" fused
+ * with the append): for every active sequence  k = RoPE(x W_k^T),  v = x W_v^T  are computed and
+ * written, rounded to bf16, straight into the next free slot of the decode pool.  The decode step
+ * that follows must be called with k_new = v_new = NULL for these sequences.
+ *   x              device pointer [batch, hidden] bf16           the layer's input of this step
+ *   w_k, w_v       device pointers [n_kv_heads*head_dim, hidden] bf16, one row per output feature
+ *                  (the layout of a linear layer's weight), feature = kv_head*head_dim + i
+ *   hidden         multiple of 256
+ *   rope_positions device pointer int32[batch]: absolute position of the token (prompt length +
+ *                  tokens generated so far, as the model counts them)
+ *   rope_theta     base of the rotary encoding.  Convention (the paper leaves positional encoding
+ *                  to the model): rotate-half -- for i < head_dim/2 and angle pos*theta^(-2i/head_dim),
+ *                  (k_i, k_{i+D/2}) -> (k_i cos - k_{i+D/2} sin, k_{i+D/2} cos + k_i sin); v is not rotated.
+ * fp32 accumulation, the rotation in double precision.  MKV_BF16 contexts only (MKV_ERR_ARG).
+ * MKV_ERR_STATE if a projected row is still waiting for its decode step; MKV_ERR_CAPACITY if an
+ * active sequence has no free decode slot. */
+int mkv_project_append(mkv_ctx* ctx, int layer, const void* x, const void* w_k, const void* w_v, int hidden,
+                       const int32_t* rope_positions, float rope_theta, const uint8_t* seq_mask);
+
 /* One pass of Algorithm 1 for every active sequence of one layer.
  *   q     device pointer [batch, n_q_heads, head_dim]   the step's queries
  *   k_new device pointer [batch, n_kv_heads, head_dim]  appended to the decode pool with I = 0
- *   v_new device pointer [batch, n_kv_heads, head_dim]
+ *   v_new device pointer [batch, n_kv_heads, head_dim]  (both NULL: mkv_project_append has put the
+ *                                                       rows in place; MKV_ERR_STATE if it has not,
+ *                                                       or if it has and they are given)
  *   out   device pointer [batch, n_q_heads, head_dim]   Att_t of Eq. 2 (rows of inactive
  *                                                       sequences are left untouched)
  *   seq_mask host pointer [batch] or NULL; 0 = sequence skipped this step (no append, no update)

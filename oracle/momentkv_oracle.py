@@ -29,6 +29,10 @@ Readings taken where the paper is silent or ambiguous (each also listed in the d
       hands in float32 (the precision the device keeps scores in), the state itself stays fp64.
   R10 score_mode "per_kv_head" (a variant, not the paper): each KV head keeps its own score
       vector, averaged over its own G query heads, and evicts independently.
+  R11 Alg. 1 starts from ComputeQKV(x_t) and leaves the projections and the positional encoding
+      to the model.  project_kv() states the usual choice for the models the paper runs: linear
+      maps k = W_k x, v = W_v x and a rotary encoding of k in the rotate-half layout -- feature i
+      of a head pairs with feature i + D/2, angle pos * theta^(-2i/D).
 
 Pins: tests/test_oracle_*.py (closed forms, invariants, a library SDPA, exhaustive subset
 search).  The multi-step trajectory as a whole is "parity unpinned" against any published
@@ -37,6 +41,31 @@ number: the paper prints no worked example; it is pinned piecewise by those test
 from __future__ import annotations
 
 import numpy as np
+
+
+# ----------------------------------------------------------------------------------------------
+# Alg. 1, first line: the token's key and value (R11)
+# ----------------------------------------------------------------------------------------------
+
+def rotary(k: np.ndarray, pos: int, theta: float) -> np.ndarray:
+    """Rotary encoding of k [..., D] at position pos, rotate-half layout: for i < D/2 the pair
+    (k[i], k[i + D/2]) is turned by the angle pos * theta**(-2i/D)."""
+    k = np.asarray(k, dtype=np.float64)
+    D = k.shape[-1]
+    half = D // 2
+    ang = float(pos) * np.power(float(theta), -2.0 * np.arange(half) / D)
+    c, s_ = np.cos(ang), np.sin(ang)
+    lo, hi = k[..., :half], k[..., half:]
+    return np.concatenate([lo * c - hi * s_, hi * c + lo * s_], axis=-1)
+
+
+def project_kv(x: np.ndarray, Wk: np.ndarray, Wv: np.ndarray, pos: int, theta: float, n_kv_heads: int):
+    """k [Hkv, D] = rotary(W_k x), v [Hkv, D] = W_v x for one token (Alg. 1 ComputeQKV, the K and V
+    part).  x [hidden]; Wk, Wv [Hkv*D, hidden], feature = kv_head * D + i."""
+    x = np.asarray(x, dtype=np.float64)
+    k = (np.asarray(Wk, dtype=np.float64) @ x).reshape(n_kv_heads, -1)
+    v = (np.asarray(Wv, dtype=np.float64) @ x).reshape(n_kv_heads, -1)
+    return rotary(k, pos, theta), v
 
 
 # ----------------------------------------------------------------------------------------------

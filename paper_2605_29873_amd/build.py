@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libmkv.so")
-SOURCES = ["mkv_api.hip", "mkv_attn.hip", "mkv_attn_mq.hip", "mkv_evict.hip"]
+SOURCES = ["mkv_api.hip", "mkv_attn.hip", "mkv_attn_mq.hip", "mkv_evict.hip", "mkv_project.hip"]
 
 # packed-fp32 instructions are switched off on purpose; hipcc's host pass warns that it does not
 # know the feature, which is harmless

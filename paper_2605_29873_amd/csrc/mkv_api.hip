@@ -29,6 +29,7 @@ struct Layout {
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, evict_key, total;
   size_t p_score, p_pos, p_map, p_info;   // prompt compression: one sequence at a time
+  size_t proj_part;                       // partial sums of the fused k/v projection (bf16 contexts)
   int cap, HL, passes, max_groups;
   int S;                  // score vectors per sequence
   int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
@@ -148,6 +149,7 @@ Layout make_layout(const mkv_config* c) {
     L.p_map = take((size_t)c->max_prefill * 4);
     L.p_info = take(4 * 4);      // (first moved slot, new size), then the row count the kernels read
   }
+  if (c->dtype == MKV_BF16) L.proj_part = take((size_t)4 * B * 2 * Hkv * D * 4);
   L.total = o;
   return L;
 }
@@ -181,6 +183,7 @@ struct mkv_ctx {
   std::vector<int32_t> h_mlen, h_nd, h_last_n;  // [L*B]; h_last_n [B]: pool size seen by the last step
   std::vector<int64_t> h_step;
   std::vector<uint8_t> frozen;
+  std::vector<uint8_t> in_pool;   // [L*B]: mkv_project_append has written the next token's row already
   int last_layer;
   int view;            // score vector the read/write helpers address (mkv_set_score_view)
   int last_q_len;      // query rows of the step taken last
@@ -294,7 +297,10 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
          void* out, const uint8_t* seq_mask) {
   if (!c) return MKV_ERR_ARG;
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
-  if (!q || !k_new || !v_new || !out) return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must not be NULL");
+  if (!q || !out) return fail(c, MKV_ERR_ARG, "q and out must not be NULL");
+  if ((k_new == nullptr) != (v_new == nullptr)) return fail(c, MKV_ERR_ARG, "k_new and v_new must be given together");
+  const bool rows_in_pool = k_new == nullptr;   // mkv_project_append has produced the new rows
+  if (rows_in_pool && q_len != 1) return fail(c, MKV_ERR_ARG, "k_new and v_new must not be NULL");
   const int B = c->cfg.batch;
   const int G = c->cfg.n_q_heads / c->cfg.n_kv_heads;
   int passes = c->lay.passes;
@@ -316,6 +322,10 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     }
     if (seq_mask && !seq_mask[b]) continue;
     const size_t i = (size_t)layer * B + b;
+    if ((c->in_pool[i] != 0) != rows_in_pool)
+      return fail(c, MKV_ERR_STATE, rows_in_pool
+                  ? fmt("sequence %d: no row from mkv_project_append is waiting, k_new and v_new are needed", b)
+                  : fmt("sequence %d: mkv_project_append has appended this step's row, pass k_new = v_new = NULL", b));
     if (c->h_nd[i] + q_len > c->lay.cap)
       return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: %d of %d decode slots used, %d more needed", b,
                                            c->h_nd[i], c->lay.cap, q_len));
@@ -369,6 +379,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     c->h_nd[i] += q_len;
     c->h_step[i] += q_len;
     c->frozen[i] = 1;
+    c->in_pool[i] = 0;
     c->h_last_n[b] = c->h_nd[i];
   }
   c->last_layer = layer;
@@ -436,7 +447,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
   s.scale_log2 = (float)(scale * 1.4426950408889634074);
   const size_t LB = (size_t)cfg->n_layers * cfg->batch;
-  c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0);
+  c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0); c->in_pool.assign(LB, 0);
   c->h_last_n.assign(cfg->batch, 0);
   hipError_t e = configure_kernels();
   {
@@ -552,6 +563,36 @@ int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scor
   return MKV_OK;
 }
 
+int mkv_project_append(mkv_ctx* c, int layer, const void* x, const void* w_k, const void* w_v, int hidden,
+                       const int32_t* rope_positions, float rope_theta, const uint8_t* seq_mask) {
+  if (!c) return MKV_ERR_ARG;
+  if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
+  if (!x || !w_k || !w_v || !rope_positions) return fail(c, MKV_ERR_ARG, "x, w_k, w_v and rope_positions must not be NULL");
+  if (c->cfg.dtype != MKV_BF16) return fail(c, MKV_ERR_ARG, "mkv_project_append needs MKV_BF16");
+  if (hidden < 256 || hidden % 256 != 0) return fail(c, MKV_ERR_ARG, "hidden must be a positive multiple of 256");
+  if (!(rope_theta > 1.0f) || isinf(rope_theta)) return fail(c, MKV_ERR_ARG, "rope_theta must be finite and above 1");
+  const int B = c->cfg.batch;
+  SeqMask mask;
+  memset(&mask, 0, sizeof mask);
+  int n_active = 0;
+  for (int b = 0; b < B; ++b) {
+    if (seq_mask && !seq_mask[b]) continue;
+    const size_t i = (size_t)layer * B + b;
+    if (c->in_pool[i]) return fail(c, MKV_ERR_STATE, fmt("sequence %d: the previous projected row has not been consumed by a decode step", b));
+    if (c->h_nd[i] >= c->lay.cap)
+      return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: decode pool is full (%d slots)", b, c->lay.cap));
+    mask.w[b >> 6] |= 1ull << (b & 63);
+    ++n_active;
+  }
+  if (n_active == 0) return MKV_OK;
+  hipError_t e = launch_project_append(c->shape, layer_view(c, layer), mask, x, w_k, w_v, rope_positions,
+                                       (float*)(c->arena + c->lay.proj_part), hidden, rope_theta, c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "projection launch");
+  for (int b = 0; b < B; ++b)
+    if (mask.active(b)) c->in_pool[(size_t)layer * B + b] = 1;
+  return MKV_OK;
+}
+
 int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, const void* v_new,
                     void* out, const uint8_t* seq_mask) {
   return step(c, layer, 1, c && c->lay.mfma_single, q, k_new, v_new, out, seq_mask);
@@ -572,8 +613,12 @@ int mkv_evict(mkv_ctx* c, int layer, int seq) {
     return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
-  for (int b = 0; b < c->cfg.batch; ++b)
-    if (seq < 0 || b == seq) mask.w[b >> 6] |= 1ull << (b & 63);
+  for (int b = 0; b < c->cfg.batch; ++b) {
+    if (seq >= 0 && b != seq) continue;
+    if (c->in_pool[(size_t)layer * c->cfg.batch + b])
+      return fail(c, MKV_ERR_STATE, fmt("sequence %d: a projected row is waiting for its decode step", b));
+    mask.w[b >> 6] |= 1ull << (b & 63);
+  }
   return run_evict(c, layer, mask, c->cfg.decode_budget);
 }
 
@@ -640,6 +685,7 @@ int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v
   c->h_nd[i] = n;
   c->h_step[i] = next_step;
   c->frozen[i] = 1;
+  c->in_pool[i] = 0;
   return MKV_OK;
 }
 

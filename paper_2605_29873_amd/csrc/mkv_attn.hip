@@ -174,7 +174,9 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     const int ntp = (p1 - p0 + TK - 1) / TK;
     const int ntd = (d1 - d0 + TK - 1) / TK;
     const int ntile = ntp + ntd;
-    const int jnew = n0;
+    // the new row: from k_new / v_new, or already in the pool when a producer kernel wrote it
+    // there (k_new == nullptr): then no slot is special
+    const int jnew = a.k_new ? n0 : -1;
 
     const size_t head_row = (size_t)b * s.Hkv + g;
     const char* kpre = (const char*)a.lv.Kp + head_row * (size_t)s.pstride * ROWB;

@@ -135,11 +135,13 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int d0 = max(ka, M) - M, d1 = max(ke, M) - M;
     // three kinds of tiles: prefill keys [p0, p1); decode keys that are in the pool already
     // [d0, dp); and appended tokens [a0, d1) of this call, which are still in k_new / v_new
-    const int dp = min(d1, n0);
+    // (k_new == nullptr: a producer kernel has written the new row into the pool already)
+    const bool in_pool = a.k_new == nullptr;
+    const int dp = in_pool ? d1 : min(d1, n0);
     const int a0 = max(d0, n0);
     const int ntp = (p1 - p0 + kTK - 1) / kTK;
     const int ntd = (max(dp - d0, 0) + kTK - 1) / kTK;
-    const int nta = d1 > a0 ? 1 : 0;                       // Q <= 16 < kTK: one tile holds them
+    const int nta = (!in_pool && d1 > a0) ? 1 : 0;         // Q <= 16 < kTK: one tile holds them
     const int ntile = ntp + ntd + nta;
     const int nrows = min(a.HP, s.G - pass * a.HP) * Q;   // real rows of this pass
     // logit staging window: as many keys as the real rows leave room for (whole tiles)
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // Append (Alg. 1): the work-group whose piece holds new slots stores their rows for later
     // steps; in this step every reader takes them from k_new / v_new.
     if (pass == 0) {
-      for (int idx = tid; idx < (d1 - a0) * 2 * kNV; idx += kThreads) {
+      for (int idx = tid; idx < (in_pool ? 0 : (d1 - a0) * 2 * kNV); idx += kThreads) {
         const int row = idx / (2 * kNV), rem = idx - row * 2 * kNV;
         const int vsel = rem / kNV, vec = rem - vsel * kNV;
         const int jn = a0 + row;

@@ -111,6 +111,14 @@ hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& 
 hipError_t launch_evict_one(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
                             hipStream_t st, const KernelTimer* tm = nullptr);
 
+// k/v projection + rotary encoding of the appended token, written into slot nd[b] of the decode
+// pool (bf16 only; hidden a multiple of 256).
+// `part`: scratch of project_ksplit(hidden) * B * 2 * Hkv * D floats.
+int project_ksplit(int hidden);
+hipError_t launch_project_append(const Shape& s, const LayerView& lv, const SeqMask& mask, const void* x,
+                                 const void* wk, const void* wv, const int32_t* rope_pos, float* part,
+                                 int hidden, float rope_theta, hipStream_t st, const KernelTimer* tm = nullptr);
+
 hipError_t configure_kernels();
 
 inline int head_lanes(int G) { return G == 1 ? 1 : G == 2 ? 2 : G <= 4 ? 4 : 8; }

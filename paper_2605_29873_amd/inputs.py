@@ -28,6 +28,8 @@ _ROLE_STEP = 2
 _ROLE_DIRECTION = 3
 _ROLE_LAYOUT = 4
 _ROLE_SNAPSHOT = 5
+_ROLE_WEIGHT = 6
+_ROLE_HIDDEN = 7
 
 NEVER = 2**31 - 1
 
@@ -234,3 +236,21 @@ def decode_snapshot(wl: Workload, layer: int, seq: int, n_d: int, t_now: int):
     pos = np.sort(g.choice(t_now, size=n_d, replace=False)).astype(np.int32)
     scores = (g.random(n_d, dtype=np.float32) * np.float32(1e-3)).astype(np.float32)
     return k, v, scores, pos
+
+
+def projection_weights(wl: Workload, layer: int, hidden: int):
+    """W_k, W_v [Hkv*D, hidden] of one layer (one row per output feature), N(0, 1/hidden) so that
+    the projected rows have unit variance like the other synthetic keys; storage-rounded."""
+    g = _gen(wl, layer, 0, _ROLE_WEIGHT, hidden)
+    n = wl.n_kv_heads * wl.head_dim
+    sd = np.float32(1.0 / np.sqrt(hidden))
+    wk = g.standard_normal((n, hidden), dtype=np.float32) * sd
+    wv = g.standard_normal((n, hidden), dtype=np.float32) * sd
+    return to_storage_values(wk, wl.dtype), to_storage_values(wv, wl.dtype)
+
+
+def step_hidden(wl: Workload, layer: int, t: int, hidden: int) -> np.ndarray:
+    """The layer input x_t of every sequence at decode step t: [B, hidden], N(0,1), storage-rounded."""
+    rows = [_gen(wl, layer, s, _ROLE_HIDDEN, t).standard_normal(hidden, dtype=np.float32)
+            for s in range(wl.batch)]
+    return to_storage_values(np.stack(rows), wl.dtype)
