@@ -151,3 +151,11 @@ def test_argument_and_state_errors(mkv):
         make_ctx(mkv, X.scaled(wl, dtype="f32"), manual_evict=True, max_q_len=2)
     with pytest.raises(mkv.MkvError):
         make_ctx(mkv, X.scaled(wl, head_dim=64), manual_evict=True, max_q_len=2)
+
+
+def test_batch_beyond_the_inline_length_table(mkv):
+    wl = _small(4, 2, batch=40, prefill_min=0, prefill_max=120)
+    ls = Lockstep(mkv, wl, seqs=[0, 31, 32, 39], active=range(wl.batch), max_q_len=3)
+    ls.prefill()
+    _chunks(ls, 36, [3, 1, 2], check_abar=True)
+    assert ls.evictions >= 4 * 2

@@ -258,3 +258,17 @@ def test_cfg3_full_size_sampled_on_the_vector_alu_kernel(mkv):
     ls.load_snapshot(wl.evict_trigger - 2, 5000)
     _run(ls, 4, t0=5000)
     assert ls.evictions == 2
+
+
+@pytest.mark.parametrize("dtype,D,G", [("bf16", 128, 4), ("f32", 64, 2)])
+def test_batches_beyond_the_inline_length_table(mkv, dtype, D, G):
+    # up to 32 sequences the per-sequence lengths travel with the launch arguments; larger batches
+    # read them from device memory and build the prefix offsets in the kernel
+    wl = X.Workload("wide", batch=70, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=D, dtype=dtype,
+                    prefill_min=0, prefill_max=90, decode_budget=10, evict_trigger=13, recent_window=2,
+                    alpha=0.7, steps=0, hh_prob=0.05)
+    active = [s for s in range(wl.batch) if s % 9 != 4]          # a few holes in the batch
+    ls = Lockstep(mkv, wl, seqs=[0, 33, 34, 69], active=active)
+    ls.prefill()
+    _run(ls, 30, check_abar=True)
+    assert ls.evictions >= 4 * 3
