@@ -625,6 +625,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
   const int Hs = s.H / s.S;
   const float inv_Hs = 1.0f / (float)Hs;
   const bool pick_one = s.trigger == s.budget && n1 == s.budget + 1;
+  __shared__ unsigned long long key_slots[4];
   for (int sv = 0; sv < s.S; ++sv) {
     unsigned long long key = ~0ull;
     if (j < n1) {
@@ -658,7 +659,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs
       if (j == n0) a.lv.pos[si] = a.lv.tpos[b];
       if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
     }
-    if (pick_one) wave_min_key_to(key, a.sc.evict_key + b * s.S + sv, lane);
+    if (pick_one) block_min_key_to(key, a.sc.evict_key + b * s.S + sv, key_slots, tid);
   }
   if (j == n0) a.lv.tpos[b] += 1;
 }

@@ -532,10 +532,15 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   constexpr int kPre = 32;
   const bool pre = Q == 1 && s.H <= kPre;
   float xpre[kPre];
+  constexpr int kPreS = 8;               // score vectors whose previous value is fetched up front too
+  float ipre[kPreS];
   if (pre && jb + tid < n1) {
     const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
 #pragma unroll
     for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
+#pragma unroll
+    for (int sv = 0; sv < kPreS; ++sv)
+      ipre[sv] = (sv < s.S && jb + tid < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + jb + tid] : 0.f;
   }
   // normalisers of all rows, `parts` threads per row; smem: [rows], then [parts][rc]
   {
@@ -583,11 +588,19 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   // (mean over the G heads of the group): vector sv covers heads [sv*Hs, (sv+1)*Hs).
   const int Hs = s.H / s.S;
   const float inv_Hs = 1.0f / (float)Hs;
+  __shared__ unsigned long long key_slots[4];
   for (int sv = 0; sv < s.S; ++sv) {
     unsigned long long key = ~0ull;
     if (j < n1) {
       const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
-      float I = (j < n0) ? a.lv.score[si] : 0.f;
+      float I;
+      if (pre && sv < kPreS) {
+        I = ipre[0];
+#pragma unroll
+        for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
+      } else {
+        I = (j < n0) ? a.lv.score[si] : 0.f;
+      }
       float abar = 0.f;
       if (pre) {
         float sum0 = 0.f, sum1 = 0.f;
@@ -626,7 +639,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       a.sc.abar[si] = abar;
       if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
     }
-    if (pick_one) wave_min_key_to(key, a.sc.evict_key + b * s.S + sv, lane);
+    if (pick_one) block_min_key_to(key, a.sc.evict_key + b * s.S + sv, key_slots, tid);
   }
 }
 

@@ -156,14 +156,25 @@ __device__ __forceinline__ unsigned long long evict_key_of(float score, int slot
   return ((unsigned long long)ordered_key(__builtin_bit_cast(uint32_t, score)) << 32) | (uint32_t)slot;
 }
 
-// Minimum of `key` over the wave, merged into *dst by lane 0 (~0 = no candidate).
-__device__ __forceinline__ void wave_min_key_to(unsigned long long key, unsigned long long* dst, int lane) {
+// Minimum of `key` over a 256-thread work-group, merged into *dst with one atomic (~0 = no
+// candidate): atomics of many waves on one address queue up behind each other.  Every thread of the
+// work-group must call it; `slots` is LDS for four values.
+__device__ __forceinline__ void block_min_key_to(unsigned long long key, unsigned long long* dst,
+                                                 unsigned long long* slots, int tid) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
     const unsigned long long o = __shfl_xor(key, off);
     key = o < key ? o : key;
   }
-  if (lane == 0 && key != ~0ull) atomicMin(dst, key);
+  __syncthreads();                      // slots may still be read from the previous call
+  if ((tid & 63) == 0) slots[tid >> 6] = key;
+  __syncthreads();
+  if (tid == 0) {
+    unsigned long long m = slots[0];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) m = slots[w] < m ? slots[w] : m;
+    if (m != ~0ull) atomicMin(dst, m);
+  }
 }
 
 }  // namespace dev
