@@ -91,7 +91,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   __shared__ long long offs[kMaxBatch + 1];
   __shared__ float sm_logit[kLogitFloats + 16 * 4];   // rows of SK + 4 floats (the pad spreads the banks)
   __shared__ float sm_new[16][kTK + 4];      // logits of the appended tokens
-  __shared__ float sm_part[WPB / 2][34][64];   // a wave's accumulators, reference and sum, lane-major
+  __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane, &a.lens);
   __syncthreads();
   if (blockIdx.x == 0) {
@@ -380,49 +380,47 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
 
-    // waves -> one partial, halving the number of live waves per round
+    // waves -> one partial per piece in a single pass: every wave leaves its accumulators,
+    // reference and sum in LDS (lane-major, conflict-free); after one barrier, thread
+    // (lane, i, q) merges four consecutive output elements over the waves and stores them.
+    {
+      float (*dst)[64] = sm_part[wave];
 #pragma unroll
-    for (int stride = WPB / 2; stride >= 1; stride >>= 1) {
-      if (wave >= stride && wave < 2 * stride) {
-        float (*dst)[64] = sm_part[wave - stride];
+      for (int dc = 0; dc < 8; ++dc)
 #pragma unroll
-        for (int dc = 0; dc < 8; ++dc)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) dst[dc * 4 + i][lane] = acc[dc][i];
-        dst[32][lane] = m_run;
-        dst[33][lane] = l_run;
-      }
-      __syncthreads();
-      if (wave < stride) {
-        float (*src)[64] = sm_part[wave];
-        const float mo = src[32][lane], lo = src[33][lane];
-        const float mx = fmaxf(m_run, mo);
-        // a wave without visible keys has reference -inf
-        const float wa = (m_run == -INFINITY) ? 0.f : fast_exp2(m_run - mx);
-        const float wb = (mo == -INFINITY) ? 0.f : fast_exp2(mo - mx);
-#pragma unroll
-        for (int dc = 0; dc < 8; ++dc)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[dc][i] = fmaf(wa, acc[dc][i], wb * src[dc * 4 + i][lane]);
-        l_run = fmaf(wa, l_run, wb * lo);
-        m_run = mx;
-      }
-      __syncthreads();
+        for (int i = 0; i < 4; ++i) dst[dc * 4 + i][lane] = acc[dc][i];
+      dst[32][lane] = m_run;
+      dst[33][lane] = l_run;
     }
-    if (wave == 0 && r16 < nrows) {
-      const size_t slot = (size_t)blockIdx.x + (size_t)b * units + ul;
-      float* po = a.sc.part_o + (slot * 16 + r16) * kD;
+    __syncthreads();
+    for (int item = tid; item < 64 * 8; item += kThreads) {
+      const int ln = item & 63, iq = item >> 6;       // source lane; (i, q) = (iq & 3, iq >> 2)
+      const int row = ln & 15, jj = ln >> 4, i = iq & 3, q = iq >> 2;
+      if (row < nrows) {
+        float mx = sm_part[0][32][ln];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float4* dst = reinterpret_cast<float4*>(po + 8 * (4 * j4 + i));
-        dst[0] = make_float4(acc[0][i], acc[1][i], acc[2][i], acc[3][i]);
-        dst[1] = make_float4(acc[4][i], acc[5][i], acc[6][i], acc[7][i]);
-      }
-      if (j4 == 0) {
-        a.sc.part_ml[(slot * 16 + r16) * 2] = m_run;
-        a.sc.part_ml[(slot * 16 + r16) * 2 + 1] = l_run;
+        for (int w = 1; w < WPB; ++w) mx = fmaxf(mx, sm_part[w][32][ln]);
+        float o[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;
+#pragma unroll
+        for (int w = 0; w < WPB; ++w) {
+          const float mw = sm_part[w][32][ln];
+          // a wave without visible keys has reference -inf; if no wave had any, mx is -inf as well
+          const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - mx);
+          lt = fmaf(e, sm_part[w][33][ln], lt);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) o[c] = fmaf(e, sm_part[w][(4 * q + c) * 4 + i][ln], o[c]);
+        }
+        const size_t slot = (size_t)blockIdx.x + (size_t)b * units + ul;
+        // accumulator (dc, i) of lane (row, jj) is output element 8 * (4 jj + i) + dc
+        *reinterpret_cast<float4*>(a.sc.part_o + (slot * 16 + row) * kD + 8 * (4 * jj + i) + 4 * q) =
+            make_float4(o[0], o[1], o[2], o[3]);
+        if (jj == 0 && iq == 0) {
+          a.sc.part_ml[(slot * 16 + row) * 2] = mx;
+          a.sc.part_ml[(slot * 16 + row) * 2 + 1] = lt;
+        }
       }
     }
+    __syncthreads();   // sm_part is reused by the next piece
     r0 += ke - ka;
   }
 }
