@@ -28,7 +28,10 @@ constexpr int kD = 128;
 constexpr int kRowB = kD * 2;      // bytes per K or V row
 constexpr int kNV = kRowB / 16;    // 16-byte vectors per row
 constexpr int kTK = 32;            // keys per wave tile
-constexpr int kLogitFloats = 6144;  // LDS floats that stage decode logits: nrows x (keys per window)
+// LDS floats that stage decode logits: real rows x (keys per window).  48 KiB: a 16-row pass gets
+// 768-key windows (fewer drains: 86 -> 82 us at four query rows on the Llama-shaped layer); the
+// kernel runs one work-group per compute unit anyway (registers)
+constexpr int kLogitFloats = 12288;
 
 struct MqArgs {
   Shape s;
@@ -651,7 +654,7 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 }
 
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  // waves per work-group: variant 17 = 4, default 8
+  // waves per work-group: variant 17 = 4, default 8 (12 waves at 168 registers: 2 % slower)
   if (a.s.variant == 17) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
   return launch_mq_w<8>(a, n_groups, occupancy, st, tm);
 }
