@@ -58,6 +58,9 @@ std::string check_config(const mkv_config* c) {
   if (c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 64 or 128";
   if (c->dtype != MKV_F32 && c->dtype != MKV_BF16) return "dtype must be MKV_F32 or MKV_BF16";
   if (c->max_prefill < 0) return "max_prefill must be >= 0";
+  // one (sequence, KV head) region is addressed with 32-bit byte offsets
+  if ((int64_t)c->max_prefill * c->head_dim * 4 >= (int64_t)1 << 31)
+    return "max_prefill * head_dim must stay below 2^29 elements per KV head";
   if (c->decode_budget < 1) return "decode_budget must be >= 1";
   if (c->evict_trigger < c->decode_budget) return "evict_trigger must be >= decode_budget";
   if (c->recent_window < 0 || c->recent_window > c->decode_budget)

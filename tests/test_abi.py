@@ -62,7 +62,7 @@ def test_required_bytes_covers_the_pools(lib):
     dict(evict_trigger=B.MKV_NEVER_EVICT, decode_capacity=64),              # not above the budget
     dict(decode_capacity=70),                                               # below trigger + 1
     dict(decode_budget=20000, evict_trigger=20000),                         # above the supported pool
-    dict(batch=5000), dict(softmax_scale=-1.0), dict(arena=12345, arena_bytes=1 << 30),
+    dict(batch=5000), dict(max_prefill=1 << 24), dict(softmax_scale=-1.0), dict(arena=12345, arena_bytes=1 << 30),
 ])
 def test_bad_configurations_are_refused_without_touching_the_gpu(lib, bad):
     cfg = _cfg(**bad)

@@ -272,3 +272,17 @@ def test_batches_beyond_the_inline_length_table(mkv, dtype, D, G):
     ls.prefill()
     _run(ls, 30, check_abar=True)
     assert ls.evictions >= 4 * 3
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 128), ("f32", 64)])
+def test_largest_supported_batch(mkv, dtype, D):
+    # 1024 sequences (the size of the by-value sequence mask and of the in-kernel offset table),
+    # every third one inactive, tiny pools; the first, a middle and the last sequence are followed
+    wl = X.Workload("b1024", batch=1024, n_layers=1, n_q_heads=2, n_kv_heads=1, head_dim=D, dtype=dtype,
+                    prefill_min=0, prefill_max=5, decode_budget=4, evict_trigger=5, recent_window=1,
+                    alpha=0.6, steps=0, hh_prob=0.1)
+    active = [s for s in range(wl.batch) if s % 3 != 1]
+    ls = Lockstep(mkv, wl, seqs=[0, 513, 1023], active=active)
+    ls.prefill()
+    _run(ls, 12, check_abar=True)
+    assert ls.evictions >= 3 * 3
