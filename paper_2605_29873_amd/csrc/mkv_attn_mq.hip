@@ -1,9 +1,10 @@
-// Multi-query decode step on the matrix cores: q_len = Q query rows per sequence and step
-// (chunked or speculative decoding), causal among the Q appended tokens.  With the G query heads
-// that share a KV head, a pass has up to 16 rows (heads x query positions) against every key, so
-// QK^T and PV are dense 16-wide contractions and run on MFMA.  Paper: Eq. 2 (attention over the
-// prefill and decode pools), Eq. 4-6 (head mean and momentum, applied once per query row in order),
-// Algorithm 1 "append".  bf16 storage and head_dim 128 only.
+// Decode attention on the matrix cores for bf16 layers with 128-wide heads: the single-query step
+// (Q = 1) and the multi-query step (Q <= 16 query rows per sequence and call: chunked or speculative
+// decoding, causal among the Q appended tokens).  With the G query heads that share a KV head, a
+// pass has up to 16 rows (heads x query positions) against every key, so QK^T and PV are 16-wide
+// contractions and run on MFMA; what is left for the vector ALU is the softmax.  Paper: Eq. 2
+// (attention over the prefill and decode pools), Eq. 4-6 (head mean and momentum, applied once per
+// query row in order), Algorithm 1 "append".
 //
 // gfx950 only: v_mfma_f32_16x16x32_bf16.  Operand layouts (lane l, r = l % 16, j = l / 16):
 //   A[m][k] : lane holds m = r, k = 8j .. 8j+7      B[k][n] : lane holds n = r, k = 8j .. 8j+7
@@ -59,7 +60,6 @@ __device__ __forceinline__ T pick3(int seg, T x0, T x1, T x2) { return pick(seg 
 
 // Untyped buffer descriptor over `bytes` bytes at p: loads past the end return zeros.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* p, int bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, bytes, 0x00020000);
 }
