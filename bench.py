@@ -381,13 +381,13 @@ def main():
         except Exception as e:  # a side measurement must not lose the main line
             others[name] = {"error": repr(e)}
     line = {
-        "metric": "us_per_decode_step_per_layer (attn+score+evict)",
+        "metric": "\u00b5s per decode step per layer (attn+score+evict) + achieved HBM GB/s vs peak",
         "value": main_res["us_per_step_per_layer"],
         "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if wl.dtype == "f32" else "f32 accumulate over bf16 K/V",
+        "dtype": "f32" if wl.dtype == "f32" else "bf16",   # bf16 operands, fp32 accumulation and scores
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": wl.batch, "layers": wl.n_layers,
                    "heads": f"{wl.n_q_heads}q/{wl.n_kv_heads}kv x {wl.head_dim}",
