@@ -623,15 +623,22 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
           const float* nq = smem + qi * s.H + sv * Hs;
           const size_t hstride = (size_t)Q * s.cap;
           int h = 0;
-          for (; h + 7 < Hs; h += 8) {
-            float x[8];
+          for (; h + 31 < Hs; h += 32) {   // thirty-two independent loads in flight
+            float x[32];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = lq[(size_t)(h + u) * hstride];
+            for (int u = 0; u < 32; ++u) x[u] = lq[(size_t)(h + u) * hstride];
 #pragma unroll
-            for (int u = 0; u < 8; u += 2) {
+            for (int u = 0; u < 32; u += 2) {
               sum0 += fast_exp2(x[u] - nq[h + u]);
               sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
             }
+          }
+          for (; h + 3 < Hs; h += 4) {
+            float x[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[u] = lq[(size_t)(h + u) * hstride];
+            sum0 += fast_exp2(x[0] - nq[h]) + fast_exp2(x[2] - nq[h + 2]);
+            sum1 += fast_exp2(x[1] - nq[h + 1]) + fast_exp2(x[3] - nq[h + 3]);
           }
           for (; h < Hs; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
           abar = (sum0 + sum1) * inv_Hs;
