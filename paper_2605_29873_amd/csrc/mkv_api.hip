@@ -370,13 +370,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
   hipError_t e;
-  // Bytes of K and V the context's layers stream per step, against the 256 MB on-package cache:
-  // well above it the loads are marked non-temporal (86 GB context: +5 % bandwidth at 1, 2 and 4
-  // query rows); below it the next step finds the pools cached and the default policy is better
-  // (142 MB: 26 vs 34 us); in between (420 MB) the hint pays at one query row only.
-  const double step_bytes = (double)total_keys / passes * c->cfg.head_dim * 2 * 2 * c->cfg.n_layers;
-  const bool stream_nt = step_bytes > 1e9 || (step_bytes > 200e6 && q_len == 1);
-  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, stream_nt, c->stream, pe ? &t_attn : nullptr);
+  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
   if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);

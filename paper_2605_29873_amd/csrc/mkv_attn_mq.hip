@@ -47,7 +47,6 @@ struct MqArgs {
   int Q;        // query rows per sequence
   int HP;       // query heads served per pass: min(G, 16 / Q)
   int passes;   // passes per KV head: ceil(G / HP)
-  int nt;       // host's choice of the cache policy of the K and V loads (non-temporal or default)
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
@@ -82,7 +81,7 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 // The V^T operand wants, per lane, one head-dim element of 8 keys: lane (r, j) loads vector r of
 // the 8 keys it contracts and transposes 16-bit halves in registers (one byte-permute per dword).
 // The accumulators then hold O[row r][8 * (4j + i) + dc] for chunk dc, i = 0..3.
-template <int WPB, int AUX>
+template <int WPB, int AUXK, int AUXV>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   constexpr int kThreads = WPB * 64;
   const Shape& s = a.s;
@@ -240,7 +239,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       for (int h = 0; h < 2; ++h) {
         const uint32_t so = (uint32_t)(t.row0 + 16 * h) * (uint32_t)t.stride;
 #pragma unroll
-        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = buf_load16<AUX>(t.rk, t.vk + iv * 64, so);
+        for (int iv = 0; iv < 4; ++iv) kr[h][iv] = buf_load16<AUXK>(t.rk, t.vk + iv * 64, so);
       }
     };
     auto load_v = [&](int tt, int t_end, uint4 (&vr)[2][4]) __attribute__((always_inline)) {
@@ -249,7 +248,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       for (int h = 0; h < 2; ++h) {
         const uint32_t so = (uint32_t)(t.row0 + 16 * h) * (uint32_t)t.stride;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) vr[h][i] = buf_load16<AUX>(t.rv, t.vv, so + (uint32_t)(i * t.stride));
+        for (int i = 0; i < 4; ++i) vr[h][i] = buf_load16<AUXV>(t.rv, t.vv, so + (uint32_t)(i * t.stride));
       }
     };
 
@@ -653,9 +652,9 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   }
 }
 
-template <int WPB, int AUX = 0>
+template <int WPB, int AUXK = 0, int AUXV = 0>
 hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  auto kern = attn_mq_kernel<WPB, AUX>;
+  auto kern = attn_mq_kernel<WPB, AUXK, AUXV>;
   if (occupancy) return hipOccupancyMaxActiveBlocksPerMultiprocessor(occupancy, kern, WPB * 64, 0);
   if (tm) hipExtLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, a);
@@ -665,13 +664,13 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
   // waves per work-group: variant 17 = 4, default 8 (12 waves at 168 registers: 2 % slower)
   if (a.s.variant == 17) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
-  // K and V loads carry the non-temporal hint when the cache pools are larger than the on-package
-  // cache can hold from one step to the next (measured: +5 % bandwidth on an 86 GB context, and
-  // -25 % on a 142 MB one that would otherwise be served from that cache); variants 19 / 20 force
-  // the hint on / off
-  const bool nt = a.s.variant == 19 || (a.s.variant != 20 && a.nt);
-  if (nt) return launch_mq_w<8, 2>(a, n_groups, occupancy, st, tm);
-  return launch_mq_w<8>(a, n_groups, occupancy, st, tm);
+  // V loads carry the non-temporal hint, K loads do not (variant 20: neither).  A V row is read
+  // whole by one load instruction and never again in the launch; a K row is read in 64-byte pieces
+  // by four instructions, and with the hint its cache lines were sometimes dropped between them
+  // (measured traffic +2.5 %).  Llama-shaped layers: 72 -> 64 us (420 MB), 460 -> 418 us (2.7 GB
+  // per layer); neutral on a pool that fits the on-package cache.  Hint on K only or on both: worse.
+  if (a.s.variant == 20) return launch_mq_w<8, 0, 0>(a, n_groups, occupancy, st, tm);
+  return launch_mq_w<8, 0, 2>(a, n_groups, occupancy, st, tm);
 }
 
 }  // namespace
@@ -680,10 +679,9 @@ int mq_heads_per_pass(int G, int q_len) { return G < 16 / q_len ? G : 16 / q_len
 
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
-                          int keys_per_group, int n_groups, bool stream_nt, hipStream_t st,
-                          const KernelTimer* tm) {
+                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm) {
   MqArgs a;
-  a.s = s; a.lv = lv; a.sc = sc; a.lens = lens; a.nt = stream_nt;
+  a.s = s; a.lv = lv; a.sc = sc; a.lens = lens;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
   a.mask = mask; a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
