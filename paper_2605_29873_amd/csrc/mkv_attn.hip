@@ -232,8 +232,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
         const char* vp = isnew ? vnew : vbase + (size_t)j * ROWB;
 #pragma unroll
         for (int vi = 0; vi < VPL; ++vi) {
-          kr[it][vi] = ldg16(kp + (vi * LPK + c) * 16);
-          vr[it][vi] = ldg16(vp + (vi * LPK + c) * 16);
+          kr[it][vi] = ldg16_stream(kp + (vi * LPK + c) * 16);
+          vr[it][vi] = ldg16_stream(vp + (vi * LPK + c) * 16);
         }
       }
     };

@@ -67,6 +67,13 @@ __device__ __forceinline__ long long uniform(long long x) {
 }
 
 __device__ __forceinline__ uint4 ldg16(const char* p) { return *reinterpret_cast<const uint4*>(p); }
+// Same load with the non-temporal hint: for rows read once per launch by one wave, a whole row per
+// lane group, so that nothing is gained from keeping the line in a cache.
+__device__ __forceinline__ uint4 ldg16_stream(const char* p) {
+  typedef __attribute__((ext_vector_type(4))) unsigned int u4;
+  const u4 v = __builtin_nontemporal_load(reinterpret_cast<const u4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ float as_f(uint32_t u) { return __builtin_bit_cast(float, u); }
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
