@@ -20,6 +20,8 @@
  *
  * Tensor element type ("storage dtype"): MKV_F32 = IEEE float, MKV_BF16 = bfloat16 (upper 16 bits
  * of a float).  Scores are always float.  All tensors are dense, row-major, last index fastest.
+ * Device tensors handed to the library (q, k_new, v_new, out, k, v, x, w_k, w_v) must start on a
+ * 16-byte boundary (MKV_ERR_ARG otherwise): the kernels move them in 16-byte vectors.
  */
 #ifndef MKV_H
 #define MKV_H

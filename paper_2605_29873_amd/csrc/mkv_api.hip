@@ -255,6 +255,9 @@ hipError_t prof_fold(mkv_ctx* c) {
   return e;
 }
 
+// Device tensors are read and written in 16-byte vectors.
+bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
 bool bad_index(const mkv_ctx* c, int layer, int seq) {
   return layer < 0 || layer >= c->cfg.n_layers || seq < 0 || seq >= c->cfg.batch;
 }
@@ -302,6 +305,8 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!q || !out) return fail(c, MKV_ERR_ARG, "q and out must not be NULL");
   if ((k_new == nullptr) != (v_new == nullptr)) return fail(c, MKV_ERR_ARG, "k_new and v_new must be given together");
+  if (misaligned(q) || misaligned(out) || misaligned(k_new) || misaligned(v_new))
+    return fail(c, MKV_ERR_ARG, "q, k_new, v_new and out must be 16-byte aligned");
   const bool rows_in_pool = k_new == nullptr;   // mkv_project_append has produced the new rows
   if (rows_in_pool && q_len != 1) return fail(c, MKV_ERR_ARG, "k_new and v_new must not be NULL");
   const int B = c->cfg.batch;
@@ -506,6 +511,7 @@ int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void
   if (!c) return MKV_ERR_ARG;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   if (n_tokens < 0 || (n_tokens > 0 && (!k || !v))) return fail(c, MKV_ERR_ARG, "k/v NULL or n_tokens < 0");
+  if (misaligned(k) || misaligned(v)) return fail(c, MKV_ERR_ARG, "k and v must be 16-byte aligned");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
   if (c->frozen[i]) return fail(c, MKV_ERR_FROZEN, "prefill pool is frozen after the first decode step");
   if ((int64_t)c->h_mlen[i] + n_tokens > c->cfg.max_prefill)
@@ -571,6 +577,7 @@ int mkv_project_append(mkv_ctx* c, int layer, const void* x, const void* w_k, co
   if (!c) return MKV_ERR_ARG;
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!x || !w_k || !w_v || !rope_positions) return fail(c, MKV_ERR_ARG, "x, w_k, w_v and rope_positions must not be NULL");
+  if (misaligned(x) || misaligned(w_k) || misaligned(w_v)) return fail(c, MKV_ERR_ARG, "x, w_k and w_v must be 16-byte aligned");
   if (c->cfg.dtype != MKV_BF16) return fail(c, MKV_ERR_ARG, "mkv_project_append needs MKV_BF16");
   if (hidden < 256 || hidden % 256 != 0) return fail(c, MKV_ERR_ARG, "hidden must be a positive multiple of 256");
   if (!(rope_theta > 1.0f) || isinf(rope_theta)) return fail(c, MKV_ERR_ARG, "rope_theta must be finite and above 1");
@@ -665,6 +672,7 @@ int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v
   if (!c) return MKV_ERR_ARG;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   if (n < 0 || (n > 0 && (!k || !v || !scores || !positions))) return fail(c, MKV_ERR_ARG, "NULL input or n < 0");
+  if (misaligned(k) || misaligned(v)) return fail(c, MKV_ERR_ARG, "k and v must be 16-byte aligned");
   if (n > c->lay.cap) return fail(c, MKV_ERR_CAPACITY, fmt("n = %d above the decode capacity %d", n, c->lay.cap));
   if (next_step < 0 || next_step > INT32_MAX) return fail(c, MKV_ERR_ARG, "next_step out of range");
   for (int j = 0; j < n; ++j) {

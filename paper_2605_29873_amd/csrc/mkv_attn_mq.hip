@@ -441,6 +441,7 @@ struct FinishMqArgs {
 };
 
 constexpr int kFinishThreads = 256;
+constexpr int kRowsPerBlock = kFinishThreads / 64;   // output rows merged per work-group: one per wave
 
 // Where the attention kernel left the partials of row (head h, query position qi) of sequence b:
 // first slot, number of slots, and the row's position inside a slot.
@@ -459,17 +460,22 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   return p;
 }
 
-// grid (H*Q + ceil(max n_d / 256), B).  Blocks x < H*Q merge the partials of row x = qi*H + h and
-// write Att of that query row (Eq. 2).  The other blocks own 256 decode slots each: they rebuild
+// grid (ceil(H*Q / 4) + ceil(max n_d / 256), B).  The first blocks merge the partials of four rows
+// x = qi*H + h each, one wave per row, and write Att of those query rows (Eq. 2).  The other blocks
+// own 256 decode slots each: they rebuild
 // the softmax normaliser of every row, and for each slot replay the Q steps in order -- head mean
 // of the row's decode-slice probabilities (Eq. 4), then I <- alpha*I + abar (Eq. 5) -- starting
 // from I = 0 at the step that appended the slot (Eq. 6); a slot takes no update from query rows
 // that precede its own token.
+//
+// ONE: a single query row and at most 32 heads (the plain decode step of the usual layers), where a
+// slot's logits fit in registers and are fetched before the normalisers are rebuilt.
+template <bool ONE>
 __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishMqArgs a) {
   const Shape& s = a.s;
   const int b = blockIdx.y;
   if (!a.mask.active(b)) return;
-  const int Q = a.Q;
+  const int Q = ONE ? 1 : a.Q;
   // lengths and the sequence's start on the flattened key axis: with the launch arguments when the
   // batch is small (no memory round trip before the first useful load), else from memory
   const bool il = a.lens.valid;
@@ -481,45 +487,54 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int rows = s.H * Q;
   const int tid = threadIdx.x, lane = tid & 63;
   constexpr int mlstride = 16 * 2;
-  extern __shared__ float smem[];  // row blocks: piece weights; slot blocks: [rows] normalisers + scratch
+  extern __shared__ float smem[];  // slot blocks: [rows] normalisers + exchange space
 
-  if ((int)blockIdx.x < rows) {
-    const int qi = blockIdx.x / s.H, h = blockIdx.x - qi * s.H;
-    constexpr int SUB = kFinishThreads / kD;
-    const int d = tid % kD, sub = tid / kD;
+  const int row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
+  if ((int)blockIdx.x < row_blocks) {
+    // one wave per row, a lane per pair of output elements: no LDS, no barrier
+    const int x = (int)blockIdx.x * kRowsPerBlock + (tid >> 6);
+    if (x >= rows) return;
+    const int qi = x / s.H, h = x - qi * s.H;
     const RowSpan sp = row_span(a, off_b, b, h, qi, Lb);
     const int ns = sp.ns;
     const float* ml = a.sc.part_ml + (sp.slot0 * 16 + sp.row) * 2;
-    const float* po = a.sc.part_o + (sp.slot0 * 16 + sp.row) * kD + d;
-    const size_t ostride = (size_t)16 * kD;
+    const float2* po = reinterpret_cast<const float2*>(a.sc.part_o + (sp.slot0 * 16 + sp.row) * kD) + lane;
+    constexpr size_t ostride = (size_t)16 * kD / 2;
     // a row rarely has more than a few pieces: their partial outputs are fetched alongside the
     // (reference, sum) pairs rather than after the weights are known
-    const float pre0 = sub < ns ? po[(size_t)sub * ostride] : 0.f;
-    const float pre1 = sub + SUB < ns ? po[(size_t)(sub + SUB) * ostride] : 0.f;
-    float mx, L;
-    wave_merge_ml(ml, mlstride, ns, lane, mx, L);
-    for (int i = tid; i < ns; i += kFinishThreads) smem[i] = fast_exp2(ml[(size_t)i * mlstride] - mx);
-    __syncthreads();
-    float o0 = sub < ns ? smem[sub] * pre0 : 0.f;
-    float o1 = sub + SUB < ns ? smem[sub + SUB] * pre1 : 0.f;
-    int i = sub + 2 * SUB;
-    for (; i + SUB < ns; i += 2 * SUB) {
-      o0 = fmaf(smem[i], po[(size_t)i * ostride], o0);
-      o1 = fmaf(smem[i + SUB], po[(size_t)(i + SUB) * ostride], o1);
-    }
-    if (i < ns) o0 = fmaf(smem[i], po[(size_t)i * ostride], o0);
-    __shared__ float red[kFinishThreads];
-    red[tid] = o0 + o1;
-    __syncthreads();
-    if (sub == 0) {
-      float o = red[d];
+    constexpr int kPrePieces = 4;
+    float2 pre[kPrePieces];
 #pragma unroll
-      for (int k = 1; k < SUB; ++k) o += red[k * kD + d];
-      ((uint16_t*)a.out)[(((size_t)b * Q + qi) * s.H + h) * kD + d] = f32_to_bf16_rne(o / L);
+    for (int i = 0; i < kPrePieces; ++i) pre[i] = i < ns ? po[(size_t)i * ostride] : make_float2(0.f, 0.f);
+    float mx, L, m_first;                // m_first: reference of piece `lane`
+    wave_merge_ml(ml, mlstride, ns, lane, mx, L, &m_first);
+    float2 o = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < kPrePieces; ++i) {
+      const float w = fast_exp2(__shfl(m_first, i) - mx);     // 0 for a piece without visible keys
+      if (i < ns) { o.x = fmaf(w, pre[i].x, o.x); o.y = fmaf(w, pre[i].y, o.y); }
     }
-    if (tid == 0) {
+    // further pieces (few sequences spread over many work-groups), eight loads at a time
+    for (int i0 = kPrePieces; i0 < ns; i0 += 8) {
+      float2 v[8];
+      float w[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const int i = min(i0 + k, ns - 1);
+        v[k] = po[(size_t)i * ostride];
+        w[k] = ml[(size_t)i * mlstride];
+      }
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float e = i0 + k < ns ? fast_exp2(w[k] - mx) : 0.f;
+        o.x = fmaf(e, v[k].x, o.x); o.y = fmaf(e, v[k].y, o.y);
+      }
+    }
+    const uint32_t packed = (uint32_t)f32_to_bf16_rne(o.x / L) | ((uint32_t)f32_to_bf16_rne(o.y / L) << 16);
+    reinterpret_cast<uint32_t*>(a.out)[((((size_t)b * Q + qi) * s.H + h) * kD) / 2 + lane] = packed;
+    if (lane == 0) {
       a.sc.lse[((size_t)b * Q + qi) * s.H + h] = mx + log2f(L);
-      if (blockIdx.x == 0) {          // the appends become visible to the next kernel
+      if (x == 0) {                   // the appends become visible to the next kernel
         a.lv.nd[b] = n1;
         a.lv.tpos[b] += Q;
       }
@@ -527,55 +542,62 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     return;
   }
 
-  const int jb = ((int)blockIdx.x - rows) * kFinishThreads;
+  const int jb = ((int)blockIdx.x - row_blocks) * kFinishThreads;
   if (jb >= n1) return;
-  // with one query row and at most 32 heads a thread's logits fit in registers: they are fetched
-  // before the normalisers are rebuilt, so that the two memory round trips overlap
-  constexpr int kPre = 32;
-  const bool pre = Q == 1 && s.H <= kPre;
+  // ONE: the slot's logits are fetched before the normalisers are rebuilt, so that the two memory
+  // round trips overlap
+  constexpr int kPre = ONE ? 32 : 1;
   float xpre[kPre];
   constexpr int kPreS = 8;               // score vectors whose previous value is fetched up front too
   float ipre[kPreS];
-  if (pre && jb + tid < n1) {
-    const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
+  if (jb + tid < n1) {
+    if constexpr (ONE) {
+      const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
 #pragma unroll
-    for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
+      for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
+    }
 #pragma unroll
     for (int sv = 0; sv < kPreS; ++sv)
       ipre[sv] = (sv < s.S && jb + tid < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + jb + tid] : 0.f;
   }
-  // normalisers of all rows, `parts` threads per row; smem: [rows], then [parts][rc]
+  // normalisers of all rows, `parts` threads per row, each folding its share of the row's pieces
+  // into a running (reference, sum) pair from one round of loads; smem: [rows], then two arrays
+  // [parts][rc] through which the parts of a row meet
   {
     const int rc = min(rows, kFinishThreads);
     const int parts = kFinishThreads / rc;
-    float* red = smem + rows;
+    float* red_m = smem + rows;
+    float* red_l = red_m + kFinishThreads;
     for (int x0 = 0; x0 < rows; x0 += rc) {
       const int xx = tid % rc, part = tid / rc;
       const int x = x0 + xx;
       const bool on = part < parts && x < rows;
-      RowSpan sp = {0, 0, 0};
-      const float* ml = a.sc.part_ml;
-      float m_loc = -INFINITY;
       if (on) {
         const int qi = x / s.H;
-        sp = row_span(a, off_b, b, x - qi * s.H, qi, Lb);
-        ml = a.sc.part_ml + (sp.slot0 * 16 + sp.row) * 2;
-        for (int i = part; i < sp.ns; i += parts) m_loc = fmaxf(m_loc, ml[(size_t)i * mlstride]);
-        red[part * rc + xx] = m_loc;
+        const RowSpan sp = row_span(a, off_b, b, x - qi * s.H, qi, Lb);
+        const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * 16 + sp.row);
+        float m_loc = -INFINITY, l_loc = 0.f;
+        for (int i = part; i < sp.ns; i += parts) {
+          const float2 v = ml[(size_t)i * 16];
+          if (v.x > m_loc) {               // a piece without visible keys has reference -inf, sum 0
+            l_loc = fmaf(l_loc, fast_exp2(m_loc - v.x), v.y);
+            m_loc = v.x;
+          } else if (v.x != -INFINITY) {
+            l_loc = fmaf(v.y, fast_exp2(v.x - m_loc), l_loc);
+          }
+        }
+        red_m[part * rc + xx] = m_loc;
+        red_l[part * rc + xx] = l_loc;
       }
-      __syncthreads();
-      float mx = -INFINITY, l_loc = 0.f;
-      if (on) {
-        for (int p = 0; p < parts; ++p) mx = fmaxf(mx, red[p * rc + xx]);
-        for (int i = part; i < sp.ns; i += parts)
-          l_loc = fmaf(fast_exp2(ml[(size_t)i * mlstride] - mx), ml[(size_t)i * mlstride + 1], l_loc);
-      }
-      __syncthreads();
-      if (on) red[part * rc + xx] = l_loc;
       __syncthreads();
       if (on && part == 0) {
+        float mx = -INFINITY;
+        for (int p = 0; p < parts; ++p) mx = fmaxf(mx, red_m[p * rc + xx]);
         float L = 0.f;
-        for (int p = 0; p < parts; ++p) L += red[p * rc + xx];
+        for (int p = 0; p < parts; ++p) {
+          const float mp = red_m[p * rc + xx];
+          if (mp != -INFINITY) L = fmaf(red_l[p * rc + xx], fast_exp2(mp - mx), L);
+        }
         smem[x] = mx + log2f(L);   // index qi*H + h
       }
       __syncthreads();
@@ -591,12 +613,13 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int Hs = s.H / s.S;
   const float inv_Hs = 1.0f / (float)Hs;
   __shared__ unsigned long long key_slots[4];
+#pragma unroll 1
   for (int sv = 0; sv < s.S; ++sv) {
     unsigned long long key = ~0ull;
     if (j < n1) {
       const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
       float I;
-      if (pre && sv < kPreS) {
+      if (sv < kPreS) {
         I = ipre[0];
 #pragma unroll
         for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
@@ -604,7 +627,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
         I = (j < n0) ? a.lv.score[si] : 0.f;
       }
       float abar = 0.f;
-      if (pre) {
+      if constexpr (ONE) {
         float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
         for (int h = 0; h < kPre; h += 2) {
@@ -614,34 +637,51 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
         abar = (sum0 + sum1) * inv_Hs;
         I = fmaf(s.alpha, I, abar);
       } else {
-        // logits of row (h, qi) live at [b][h*Q + qi][slot]
+        // logits of row (h, qi) live at [b][h*Q + qi][slot].  The (query row, 32 heads) chunks of
+        // the slot are walked in order, one chunk ahead of the arithmetic, so that the Q updates
+        // of a slot cost about one memory round trip, not Q.  The walk is the same for every lane
+        // (all rows, heads clamped to the last one): a slot appended by this call reads the
+        // logits of the rows before its own token too -- they are there, masked only in the
+        // softmax -- and leaves them out of its score.
+        constexpr int CH = 32;
         const float* lg = a.sc.logits + ((size_t)b * rows + (size_t)sv * Hs * Q) * s.cap + j;
-        for (int qi = max(0, j - n0); qi < Q; ++qi) {
-          float sum0 = 0.f, sum1 = 0.f;
-          const float* lq = lg + (size_t)qi * s.cap;
-          const float* nq = smem + qi * s.H + sv * Hs;
-          const size_t hstride = (size_t)Q * s.cap;
-          int h = 0;
-          for (; h + 31 < Hs; h += 32) {   // thirty-two independent loads in flight
-            float x[32];
+        const size_t hstride = (size_t)Q * s.cap;
+        const int nch = (Hs + CH - 1) / CH;
+        const int q0 = j - n0;            // first row that sees the slot (<= 0: all do)
+        float xa[CH], xb[CH];
+        int qi = 0, c = 0;                // wave-uniform
+        auto fetch = [&](int qf, int cf, float (&x)[CH]) __attribute__((always_inline)) {
+          const float* src = lg + (size_t)qf * s.cap;
 #pragma unroll
-            for (int u = 0; u < 32; ++u) x[u] = lq[(size_t)(h + u) * hstride];
+          for (int u = 0; u < CH; ++u) x[u] = src[(size_t)min(cf * CH + u, Hs - 1) * hstride];
+        };
+        fetch(0, 0, xa);
+        float sum0 = 0.f, sum1 = 0.f;
+        // one chunk: request the next one into `nxt`, then consume `cur` (nothing past the last row)
+        auto stage = [&](const float (&cur)[CH], float (&nxt)[CH]) __attribute__((always_inline)) {
+          if (qi >= Q) return;
+          int qn = qi, cn = c + 1;
+          if (cn == nch) { cn = 0; qn = qi + 1; }
+          if (qn < Q) fetch(qn, cn, nxt);
+          const float* nq = smem + qi * s.H + sv * Hs + c * CH;
 #pragma unroll
-            for (int u = 0; u < 32; u += 2) {
-              sum0 += fast_exp2(x[u] - nq[h + u]);
-              sum1 += fast_exp2(x[u + 1] - nq[h + u + 1]);
+          for (int u = 0; u < CH; u += 2) {
+            if (c * CH + u < Hs) sum0 += fast_exp2(cur[u] - nq[u]);
+            if (c * CH + u + 1 < Hs) sum1 += fast_exp2(cur[u + 1] - nq[u + 1]);
+          }
+          if (cn == 0) {                 // the row is complete: Eq. 4, Eq. 5
+            const float ab = (sum0 + sum1) * inv_Hs;
+            if (qi >= q0) {
+              abar = ab;
+              I = fmaf(s.alpha, I, ab);
             }
+            sum0 = sum1 = 0.f;
           }
-          for (; h + 3 < Hs; h += 4) {
-            float x[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) x[u] = lq[(size_t)(h + u) * hstride];
-            sum0 += fast_exp2(x[0] - nq[h]) + fast_exp2(x[2] - nq[h + 2]);
-            sum1 += fast_exp2(x[1] - nq[h + 1]) + fast_exp2(x[3] - nq[h + 3]);
-          }
-          for (; h < Hs; ++h) sum0 += fast_exp2(lq[(size_t)h * hstride] - nq[h]);
-          abar = (sum0 + sum1) * inv_Hs;
-          I = fmaf(s.alpha, I, abar);
+          qi = qn; c = cn;
+        };
+        while (qi < Q) {                 // the two register sets swap roles: no copies, no early waits
+          stage(xa, xb);
+          stage(xb, xa);
         }
       }
       a.lv.score[si] = I;
@@ -705,11 +745,11 @@ hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& 
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   const int rows = s.H * q_len;
-  dim3 grid(rows + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
-  const int need = rows + kFinishThreads > s.max_groups ? rows + kFinishThreads : s.max_groups;
-  const size_t smem = (size_t)need * sizeof(float);
-  if (tm) hipExtLaunchKernelGGL(finish_mq_kernel, grid, dim3(kFinishThreads), smem, st, tm->start, tm->stop, 0, a);
-  else hipLaunchKernelGGL(finish_mq_kernel, grid, dim3(kFinishThreads), smem, st, a);
+  dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
+  const size_t smem = (size_t)(rows + 2 * kFinishThreads) * sizeof(float);   // slot blocks: normalisers + exchange
+  auto kern = (q_len == 1 && s.H <= 32) ? finish_mq_kernel<true> : finish_mq_kernel<false>;
+  if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, tm->start, tm->stop, 0, a);
+  else hipLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();
 }
 

@@ -141,14 +141,19 @@ __device__ __forceinline__ float wave_sum(float x) {
 // Softmax normaliser of one head from its per-piece (reference, sum) pairs, by one whole wave:
 // returns the common reference mx and the total sum L relative to it (both base 2).  `ml` points
 // at the head's pair in the first slot; consecutive slots are `stride` floats apart.
-__device__ __forceinline__ void wave_merge_ml(const float* ml, int stride, int ns, int lane, float& mx, float& L) {
-  float m_loc = -INFINITY;
-  for (int i = lane; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[(size_t)i * stride]);
+__device__ __forceinline__ void wave_merge_ml(const float* ml, int stride, int ns, int lane, float& mx, float& L,
+                                              float* m_first = nullptr) {
+  // the first 64 pieces (nearly always all of them) are held in registers: one round of loads
+  const float2 v = lane < ns ? *reinterpret_cast<const float2*>(ml + (size_t)lane * stride)
+                             : make_float2(-INFINITY, 0.f);
+  float m_loc = v.x;
+  for (int i = lane + 64; i < ns; i += 64) m_loc = fmaxf(m_loc, ml[(size_t)i * stride]);
   mx = wave_max(m_loc);
-  float l_loc = 0.f;
-  for (int i = lane; i < ns; i += 64)
+  float l_loc = (v.x == -INFINITY) ? 0.f : fast_exp2(v.x - mx) * v.y;
+  for (int i = lane + 64; i < ns; i += 64)
     l_loc = fmaf(fast_exp2(ml[(size_t)i * stride] - mx), ml[(size_t)i * stride + 1], l_loc);
   L = wave_sum(l_loc);
+  if (m_first) *m_first = v.x;
 }
 
 // Order-preserving map float -> uint32 (total order of the reals; -0 is folded onto +0 so that the

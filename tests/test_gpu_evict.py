@@ -106,6 +106,11 @@ def test_runtime_error_paths_leave_state_unchanged(mkv):
     assert mkv.mkv_get_lens(ctx, 0, 0) == (10, 0, 0)
     assert lib.mkv_decode_step(ctx, 0, q.data_ptr(), None, p, out.data_ptr(), None) == mkv.MKV_ERR_ARG
     assert lib.mkv_decode_step(ctx, 3, q.data_ptr(), p, p, out.data_ptr(), None) == mkv.MKV_ERR_ARG
+    # tensors move in 16-byte vectors: a pointer off that grid is refused before anything is launched
+    assert "aligned" in _err(mkv, lib.mkv_decode_step(ctx, 0, q.data_ptr() + 4, p, p, out.data_ptr(), None), ctx, mkv.MKV_ERR_ARG)
+    assert lib.mkv_decode_step(ctx, 0, q.data_ptr(), p, p + 8, out.data_ptr(), None) == mkv.MKV_ERR_ARG
+    assert lib.mkv_prefill_append(ctx, 0, 1, p + 2, p, 1) == mkv.MKV_ERR_ARG
+    assert mkv.mkv_get_lens(ctx, 0, 0) == (10, 0, 0)
     only0 = np.array([1, 0], dtype=np.uint8)
     for t in range(6):
         mkv.mkv_decode_step(ctx, 0, q.data_ptr(), p, p, out.data_ptr(), only0)
