@@ -140,7 +140,7 @@ Layout make_layout(const mkv_config* c) {
   L.part_o = take(rows * D * 4);
   L.part_ml = take(rows * 2 * 4);
   L.offs = take((B + 1) * 8);
-  L.logits = take(B * H * grow * L.cap * 4);
+  L.logits = take(B * H * grow * (((size_t)L.cap + 63) / 64 * 64) * 4);   // the matrix-core path tiles the slot axis by 64
   L.abar = take(B * L.S * L.cap * 4);
   L.lse = take(B * H * grow * 4);
   L.src_map = take(B * L.S * L.cap * 4);

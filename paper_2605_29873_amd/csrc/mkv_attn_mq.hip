@@ -34,6 +34,16 @@ constexpr int kTK = 32;            // keys per wave tile
 // kernel runs one work-group per compute unit anyway (registers)
 constexpr int kLogitFloats = 12288;
 
+// Decode logits of the matrix-core path, written by the attention kernel and read by the finishing
+// kernel: the slot axis is cut into tiles of 64, and a tile holds all rows (head x query position)
+// of its 64 slots back to back, [sequence][tile][row][64].  What one finishing wave reads -- every
+// row of 64 slots -- is then one contiguous run, not one 256-byte piece per row.
+constexpr int kLogitTile = 64;
+__device__ __forceinline__ size_t logit_index(const Shape& s, int b, int rows, int row, int slot) {
+  const int tiles = (s.cap + kLogitTile - 1) / kLogitTile;
+  return (((size_t)b * tiles + slot / kLogitTile) * rows + row) * kLogitTile + slot % kLogitTile;
+}
+
 struct MqArgs {
   Shape s;
   LayerView lv;
@@ -191,7 +201,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
 #pragma unroll
       for (int iv = 0; iv < 4; ++iv) qv[iv] = row_ok ? ldg16(qp + (4 * iv + j4) * 16) : make_uint4(0, 0, 0, 0);
     }
-    float* const logit_base = a.sc.logits + ((size_t)b * s.H + g * s.G + pass * a.HP) * Q * s.cap;
+    const int row_base = (g * s.G + pass * a.HP) * Q;      // first row of this pass among the H*Q rows
 
     float m_run = -INFINITY, l_run = 0.f;   // m_run is identical in the four lanes of a row
     f32x4_t acc[8];
@@ -364,12 +374,12 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         __syncthreads();
         for (int r = 0; r < nrows; ++r)
           for (int key = tid; key < nk; key += kThreads)
-            logit_base[(size_t)r * s.cap + d0 + wk0 + key] = sm_logit[r * SKP + key];
+            a.sc.logits[logit_index(s, b, s.H * Q, row_base + r, d0 + wk0 + key)] = sm_logit[r * SKP + key];
         if (last && nta) {
           const int nn = d1 - a0;
           for (int idx = tid; idx < nrows * nn; idx += kThreads) {
             const int r = idx / nn, key = idx - r * nn;
-            logit_base[(size_t)r * s.cap + a0 + key] = sm_new[r][key];
+            a.sc.logits[logit_index(s, b, s.H * Q, row_base + r, a0 + key)] = sm_new[r][key];
           }
         }
         if (!last) {
@@ -441,6 +451,7 @@ struct FinishMqArgs {
 };
 
 constexpr int kFinishThreads = 256;
+constexpr int kSlotsMulti = 64;       // decode slots per slot block when a call has several query rows
 constexpr int kRowsPerBlock = kFinishThreads / 64;   // output rows merged per work-group: one per wave
 
 // Where the attention kernel left the partials of row (head h, query position qi) of sequence b:
@@ -460,9 +471,9 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   return p;
 }
 
-// grid (ceil(H*Q / 4) + ceil(max n_d / 256), B).  The first blocks merge the partials of four rows
-// x = qi*H + h each, one wave per row, and write Att of those query rows (Eq. 2).  The other blocks
-// own 256 decode slots each: they rebuild
+// grid (ceil(H*Q / 4) + ceil(max n_d / slots per block), B).  The first blocks merge the partials of
+// four rows x = qi*H + h each, one wave per row, and write Att of those query rows (Eq. 2).  The other
+// blocks own 256 (single-row instantiation) or 64 decode slots each: they rebuild
 // the softmax normaliser of every row, and for each slot replay the Q steps in order -- head mean
 // of the row's decode-slice probabilities (Eq. 4), then I <- alpha*I + abar (Eq. 5) -- starting
 // from I = 0 at the step that appended the slot (Eq. 6); a slot takes no update from query rows
@@ -542,23 +553,27 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     return;
   }
 
-  const int jb = ((int)blockIdx.x - row_blocks) * kFinishThreads;
+  // slots per slot block: a thread per slot (ONE), or a lane per slot with the query rows dealt out
+  // to the four waves
+  constexpr int kSlots = ONE ? kFinishThreads : kSlotsMulti;
+  const int jb = ((int)blockIdx.x - row_blocks) * kSlots;
   if (jb >= n1) return;
+  const int j = jb + (ONE ? tid : lane);
   // ONE: the slot's logits are fetched before the normalisers are rebuilt, so that the two memory
   // round trips overlap
   constexpr int kPre = ONE ? 32 : 1;
   float xpre[kPre];
   constexpr int kPreS = 8;               // score vectors whose previous value is fetched up front too
   float ipre[kPreS];
-  if (jb + tid < n1) {
+  if (j < n1) {
     if constexpr (ONE) {
-      const float* lg0 = a.sc.logits + (size_t)b * rows * s.cap + jb + tid;
+      const float* lg0 = a.sc.logits + logit_index(s, b, rows, 0, j);
 #pragma unroll
-      for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[(size_t)h * s.cap] : 0.f;
+      for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[h * kLogitTile] : 0.f;
     }
 #pragma unroll
     for (int sv = 0; sv < kPreS; ++sv)
-      ipre[sv] = (sv < s.S && jb + tid < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + jb + tid] : 0.f;
+      ipre[sv] = (sv < s.S && j < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + j] : 0.f;
   }
   // normalisers of all rows, `parts` threads per row, each folding its share of the row's pieces
   // into a running (reference, sum) pair from one round of loads; smem: [rows], then two arrays
@@ -577,13 +592,19 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
         const RowSpan sp = row_span(a, off_b, b, x - qi * s.H, qi, Lb);
         const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * 16 + sp.row);
         float m_loc = -INFINITY, l_loc = 0.f;
-        for (int i = part; i < sp.ns; i += parts) {
-          const float2 v = ml[(size_t)i * 16];
-          if (v.x > m_loc) {               // a piece without visible keys has reference -inf, sum 0
-            l_loc = fmaf(l_loc, fast_exp2(m_loc - v.x), v.y);
-            m_loc = v.x;
-          } else if (v.x != -INFINITY) {
-            l_loc = fmaf(v.y, fast_exp2(v.x - m_loc), l_loc);
+        for (int i0 = part; i0 < sp.ns; i0 += 4 * parts) {   // four loads in flight
+          float2 v[4];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) v[k] = ml[(size_t)min(i0 + k * parts, sp.ns - 1) * 16];
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            if (i0 + k * parts >= sp.ns) continue;
+            if (v[k].x > m_loc) {          // a piece without visible keys has reference -inf, sum 0
+              l_loc = fmaf(l_loc, fast_exp2(m_loc - v[k].x), v[k].y);
+              m_loc = v[k].x;
+            } else if (v[k].x != -INFINITY) {
+              l_loc = fmaf(v[k].y, fast_exp2(v[k].x - m_loc), l_loc);
+            }
           }
         }
         red_m[part * rc + xx] = m_loc;
@@ -603,7 +624,6 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       __syncthreads();
     }
   }
-  const int j = jb + tid;
   // One token appended and exactly one to evict (trigger = budget, pool at budget + 1): the
   // selection of Eq. 8 is an arg-min over the scores computed right here; every slot block merges
   // its candidates' minimum into the vector's evict_key.
@@ -613,55 +633,59 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int Hs = s.H / s.S;
   const float inv_Hs = 1.0f / (float)Hs;
   __shared__ unsigned long long key_slots[4];
+  [[maybe_unused]] __shared__ float sm_abar[ONE ? 1 : 16][kSlotsMulti];   // head means per (query row, slot)
 #pragma unroll 1
   for (int sv = 0; sv < s.S; ++sv) {
     unsigned long long key = ~0ull;
-    if (j < n1) {
-      const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
-      float I;
-      if (sv < kPreS) {
-        I = ipre[0];
+    const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
+    float I = 0.f;                       // previous score of the slot (0 for one appended now, Eq. 6)
+    if (sv < kPreS) {
+      I = ipre[0];
 #pragma unroll
-        for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
-      } else {
-        I = (j < n0) ? a.lv.score[si] : 0.f;
-      }
-      float abar = 0.f;
-      if constexpr (ONE) {
+      for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
+    } else if (j < n0) {
+      I = a.lv.score[si];
+    }
+    if constexpr (ONE) {
+      if (j < n1) {
         float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
         for (int h = 0; h < kPre; h += 2) {
           if (h >= sv * Hs && h < (sv + 1) * Hs) sum0 += fast_exp2(xpre[h] - smem[h]);
           if (h + 1 >= sv * Hs && h + 1 < (sv + 1) * Hs) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
         }
-        abar = (sum0 + sum1) * inv_Hs;
+        const float abar = (sum0 + sum1) * inv_Hs;
         I = fmaf(s.alpha, I, abar);
-      } else {
-        // logits of row (h, qi) live at [b][h*Q + qi][slot].  The (query row, 32 heads) chunks of
-        // the slot are walked in order, one chunk ahead of the arithmetic, so that the Q updates
-        // of a slot cost about one memory round trip, not Q.  The walk is the same for every lane
-        // (all rows, heads clamped to the last one): a slot appended by this call reads the
-        // logits of the rows before its own token too -- they are there, masked only in the
-        // softmax -- and leaves them out of its score.
+        a.lv.score[si] = I;
+        a.sc.abar[si] = abar;
+        if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+      }
+    } else {
+      // Head means first, the recurrence after: wave w forms abar of query rows w, w+4, ... for
+      // its 64 slots (independent of each other, so the rows of a call are in flight together),
+      // then wave 0 applies Eq. 5 row by row.  Logits of row (h, qi) are row h*Q + qi of the slot's tile;
+      // a wave walks its (row, 32 heads) chunks one chunk ahead of the arithmetic, the same walk
+      // in every lane (heads clamped to the last one).
+      const int w = tid >> 6;
+      if (j < n1) {
         constexpr int CH = 32;
-        const float* lg = a.sc.logits + ((size_t)b * rows + (size_t)sv * Hs * Q) * s.cap + j;
-        const size_t hstride = (size_t)Q * s.cap;
+        const float* lg = a.sc.logits + logit_index(s, b, rows, sv * Hs * Q, j);
+        const int hstride = Q * kLogitTile;
         const int nch = (Hs + CH - 1) / CH;
-        const int q0 = j - n0;            // first row that sees the slot (<= 0: all do)
         float xa[CH], xb[CH];
-        int qi = 0, c = 0;                // wave-uniform
+        int qi = w, c = 0;                // wave-uniform
         auto fetch = [&](int qf, int cf, float (&x)[CH]) __attribute__((always_inline)) {
-          const float* src = lg + (size_t)qf * s.cap;
+          const float* src = lg + qf * kLogitTile;
 #pragma unroll
-          for (int u = 0; u < CH; ++u) x[u] = src[(size_t)min(cf * CH + u, Hs - 1) * hstride];
+          for (int u = 0; u < CH; ++u) x[u] = src[min(cf * CH + u, Hs - 1) * hstride];
         };
-        fetch(0, 0, xa);
+        if (qi < Q) fetch(qi, 0, xa);
         float sum0 = 0.f, sum1 = 0.f;
         // one chunk: request the next one into `nxt`, then consume `cur` (nothing past the last row)
         auto stage = [&](const float (&cur)[CH], float (&nxt)[CH]) __attribute__((always_inline)) {
           if (qi >= Q) return;
           int qn = qi, cn = c + 1;
-          if (cn == nch) { cn = 0; qn = qi + 1; }
+          if (cn == nch) { cn = 0; qn = qi + kFinishThreads / 64; }
           if (qn < Q) fetch(qn, cn, nxt);
           const float* nq = smem + qi * s.H + sv * Hs + c * CH;
 #pragma unroll
@@ -669,12 +693,8 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
             if (c * CH + u < Hs) sum0 += fast_exp2(cur[u] - nq[u]);
             if (c * CH + u + 1 < Hs) sum1 += fast_exp2(cur[u + 1] - nq[u + 1]);
           }
-          if (cn == 0) {                 // the row is complete: Eq. 4, Eq. 5
-            const float ab = (sum0 + sum1) * inv_Hs;
-            if (qi >= q0) {
-              abar = ab;
-              I = fmaf(s.alpha, I, ab);
-            }
+          if (cn == 0) {                 // the row is complete: Eq. 4
+            sm_abar[qi][lane] = (sum0 + sum1) * inv_Hs;
             sum0 = sum1 = 0.f;
           }
           qi = qn; c = cn;
@@ -684,9 +704,19 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
           stage(xb, xa);
         }
       }
-      a.lv.score[si] = I;
-      a.sc.abar[si] = abar;
-      if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+      __syncthreads();
+      if (w == 0 && j < n1) {
+        // a slot appended by this call takes no update from the rows before its own token
+        float abar = 0.f;
+        for (int qi = max(0, j - n0); qi < Q; ++qi) {
+          abar = sm_abar[qi][lane];
+          I = fmaf(s.alpha, I, abar);    // Eq. 5
+        }
+        a.lv.score[si] = I;
+        a.sc.abar[si] = abar;
+        if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+      }
+      if (sv + 1 < s.S) __syncthreads();   // the next vector reuses sm_abar
     }
     if (pick_one) block_min_key_to(key, a.sc.evict_key + b * s.S + sv, key_slots, tid);
   }
@@ -745,9 +775,11 @@ hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& 
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   const int rows = s.H * q_len;
-  dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock + (max_nd_eff + kFinishThreads - 1) / kFinishThreads, s.B);
+  const bool one = q_len == 1 && s.H <= 32;
+  const int slots = one ? kFinishThreads : kSlotsMulti;
+  dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock + (max_nd_eff + slots - 1) / slots, s.B);
   const size_t smem = (size_t)(rows + 2 * kFinishThreads) * sizeof(float);   // slot blocks: normalisers + exchange
-  auto kern = (q_len == 1 && s.H <= 32) ? finish_mq_kernel<true> : finish_mq_kernel<false>;
+  auto kern = one ? finish_mq_kernel<true> : finish_mq_kernel<false>;
   if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();

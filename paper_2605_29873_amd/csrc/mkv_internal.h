@@ -64,7 +64,8 @@ struct Scratch {
   float* part_o;      // [max_groups + B*Hkv*passes][HL][D]
   float* part_ml;     // [max_groups + B*Hkv*passes][HL][2]
   long long* offs;    // [B+1]  prefix sums of the per-sequence key counts of the last launch
-  float* logits;      // [B][H*q_len][cap] base-2 logits of decode keys (q_len = 1 in the single-query step)
+  float* logits;      // base-2 logits of decode keys: [B][H][cap] on the vector-ALU path,
+                      // [B][ceil(cap/64)][H*q_len][64] on the matrix-core path
   float* abar;        // [B][S][cap]       head-mean decode-slice attention of the last step
   float* lse;         // [B][q_len][H]     base-2 log of the softmax normaliser of the last step
   int32_t* src_map;   // [B][S][cap]       compaction map: new slot -> old slot
