@@ -33,6 +33,7 @@ struct Layout {
   int cap, HL, passes, max_groups;
   int S;                  // score vectors per sequence
   int mq_passes;          // most passes per KV head on the matrix-core kernels (0: they are not used)
+  int mq_slot_rows;       // most rows per partial slot on the matrix-core kernels
   bool mfma_single;       // mkv_decode_step runs on the matrix-core kernels
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
 };
@@ -105,8 +106,14 @@ Layout make_layout(const mkv_config* c) {
   const bool mfma_ok = c->dtype == MKV_BF16 && c->head_dim == 128;
   L.mfma_single = mfma_ok && (c->attn_variant == 0 || c->attn_variant >= 16);
   if (c->max_q_len > 0 || L.mfma_single) {
-    const int hp = mq_heads_per_pass(G, grow);           // fewest heads per pass = most passes
-    L.mq_passes = (G + hp - 1) / hp;
+    // most passes per KV head and most rows per partial slot over the call lengths in use
+    for (int ql = 1; ql <= grow; ++ql) {
+      if (ql > 1 && c->max_q_len == 0) break;
+      const int hp = mq_heads_per_pass(G, ql);
+      const int ps = (G + hp - 1) / hp;
+      if (ps > L.mq_passes) L.mq_passes = ps;
+      if (16 * mq_row_blocks(G, ql) > L.mq_slot_rows) L.mq_slot_rows = 16 * mq_row_blocks(G, ql);
+    }
   }
   const size_t es = c->dtype == MKV_BF16 ? 2 : 4;
   const size_t B = c->batch, Hkv = c->n_kv_heads, H = c->n_q_heads, D = c->head_dim;
@@ -136,7 +143,7 @@ Layout make_layout(const mkv_config* c) {
   L.max_groups = (int)(key_cap / 64 + 1 < (size_t)kMaxGroups ? key_cap / 64 + 1 : (size_t)kMaxGroups);
   const size_t slots = (size_t)L.max_groups + B * Hkv * L.passes;
   const size_t mq_slots = L.mq_passes ? (size_t)L.max_groups + B * Hkv * L.mq_passes : 0;
-  const size_t rows = slots * L.HL > mq_slots * 16 ? slots * L.HL : mq_slots * 16;   // partial rows
+  const size_t rows = slots * L.HL > mq_slots * L.mq_slot_rows ? slots * L.HL : mq_slots * L.mq_slot_rows;   // partial rows
   L.part_o = take(rows * D * 4);
   L.part_ml = take(rows * 2 * 4);
   L.offs = take((B + 1) * 8);

@@ -55,7 +55,7 @@ struct MqArgs {
   InlineLens lens;
   int R;        // keys per work-group
   int Q;        // query rows per sequence
-  int HP;       // query heads served per pass: min(G, 16 / Q)
+  int HP;       // query heads served per pass: min(G, rows per pass / Q)
   int passes;   // passes per KV head: ceil(G / HP)
 };
 
@@ -91,8 +91,12 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 // The V^T operand wants, per lane, one head-dim element of 8 keys: lane (r, j) loads vector r of
 // the 8 keys it contracts and transposes 16-bit halves in registers (one byte-permute per dword).
 // The accumulators then hold O[row r][8 * (4j + i) + dc] for chunk dc, i = 0..3.
-template <int WPB, int AUXK, int AUXV>
+//
+// NB: row blocks of 16 per pass.  With heads x query positions above 16 a pass carries two blocks
+// (32 rows): every K and V tile is then used twice, instead of reading the pool in two passes.
+template <int WPB, int AUXK, int AUXV, int NB>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
+  constexpr int kRows = 16 * NB;         // rows of a pass = rows of a partial slot
   constexpr int kThreads = WPB * 64;
   const Shape& s = a.s;
   const int tid = threadIdx.x;
@@ -103,8 +107,11 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   const int Q = a.Q;
   const int units = s.Hkv * a.passes;
   __shared__ long long offs[kMaxBatch + 1];
-  __shared__ float sm_logit[kLogitFloats + 16 * 4];   // rows of SK + 4 floats (the pad spreads the banks)
-  __shared__ float sm_new[16][kTK + 4];      // logits of the appended tokens
+  // two row blocks: what LDS is left goes into the window (32 rows x 576 keys), since every drain
+  // stops the work-group's stream
+  constexpr int kWindow = NB > 1 ? kLogitFloats * 3 / 2 : kLogitFloats;
+  __shared__ float sm_logit[kWindow + kRows * 4];   // rows of SK + 4 floats (the pad spreads the banks)
+  __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
   __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane, &a.lens);
   __syncthreads();
@@ -159,7 +166,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int ntile = ntp + ntd + nta;
     const int nrows = min(a.HP, s.G - pass * a.HP) * Q;   // real rows of this pass
     // logit staging window: as many keys as the real rows leave room for (whole tiles)
-    const int SK = (kLogitFloats / nrows) & ~(kTK - 1);
+    const int SK = (kWindow / nrows) & ~(kTK - 1);
     const int WT = SK / kTK;
     const int SKP = SK + 4;
 
@@ -192,21 +199,30 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
     }
 
-    // query rows: row r = (head inside the pass) * Q + (query position)
-    const int hl = r16 / Q, qi = r16 - hl * Q;
-    uint4 qv[4];
-    {
-      const bool row_ok = r16 < nrows;
-      const char* qp = a.q + (((size_t)b * Q + qi) * s.H + g * s.G + pass * a.HP + hl) * kRowB;
+    // query rows: row r = (head inside the pass) * Q + (query position); this lane serves rows
+    // r16 + 16 * nb
+    int qi[NB];
+    uint4 qv[NB][4];
 #pragma unroll
-      for (int iv = 0; iv < 4; ++iv) qv[iv] = row_ok ? ldg16(qp + (4 * iv + j4) * 16) : make_uint4(0, 0, 0, 0);
+    for (int nb = 0; nb < NB; ++nb) {
+      const int rr = r16 + 16 * nb;
+      const int hl = rr / Q;
+      qi[nb] = rr - hl * Q;
+      const bool row_ok = rr < nrows;
+      const char* qp = a.q + (((size_t)b * Q + qi[nb]) * s.H + g * s.G + pass * a.HP + hl) * kRowB;
+#pragma unroll
+      for (int iv = 0; iv < 4; ++iv) qv[nb][iv] = row_ok ? ldg16(qp + (4 * iv + j4) * 16) : make_uint4(0, 0, 0, 0);
     }
     const int row_base = (g * s.G + pass * a.HP) * Q;      // first row of this pass among the H*Q rows
 
-    float m_run = -INFINITY, l_run = 0.f;   // m_run is identical in the four lanes of a row
-    f32x4_t acc[8];
+    float m_run[NB], l_run[NB];             // m_run is identical in the four lanes of a row
+    f32x4_t acc[NB][8];
 #pragma unroll
-    for (int dc = 0; dc < 8; ++dc) acc[dc] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    for (int nb = 0; nb < NB; ++nb) {
+      m_run[nb] = -INFINITY; l_run[nb] = 0.f;
+#pragma unroll
+      for (int dc = 0; dc < 8; ++dc) acc[nb][dc] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    }
 
     // K and V come in through buffer loads: a wave-uniform descriptor per segment whose size ends
     // at the segment's last valid row -- rows past it read as zeros, so no lane clamps or branches
@@ -266,61 +282,65 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     constexpr float kSlack = 8.0f;
     // scores of one tile against the 16 rows: x[4h + i] = logit of key 16h + 4j + i (base 2), -inf
     // where masked; decode logits are staged for the score update
-    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], float (&x)[8]) __attribute__((always_inline)) {
+    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], float (&x)[NB][8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
       const int jn = pick3(seg, p1, dp, d1);
 #pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        f32x4_t sv = {0.f, 0.f, 0.f, 0.f};
+      for (int nb = 0; nb < NB; ++nb) {
+        const int rr = r16 + 16 * nb;
 #pragma unroll
-        for (int iv = 0; iv < 4; ++iv)
-          sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kr[h][iv]), as_bf16x8(qv[iv]), sv, 0, 0, 0);
-        const int key0 = jb + 16 * h + 4 * j4;
-        float4 st;
-        st.x = sv[0] * s.scale_log2; st.y = sv[1] * s.scale_log2;
-        st.z = sv[2] * s.scale_log2; st.w = sv[3] * s.scale_log2;
-        if (seg == 1 && r16 < nrows) *reinterpret_cast<float4*>(&sm_logit[r16 * SKP + (tt - ntp - win * WT) * kTK + 16 * h + 4 * j4]) = st;
-        if (seg == 2) *reinterpret_cast<float4*>(&sm_new[r16][16 * h + 4 * j4]) = st;
-        const float sx[4] = {st.x, st.y, st.z, st.w};
+        for (int h = 0; h < 2; ++h) {
+          f32x4_t sv = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int key = key0 + i;
-          // past the segment, or an appended token that comes after this row's own (causal order)
-          const bool ok = key < jn && !(seg == 2 && key - n0 > qi);
-          x[4 * h + i] = ok ? sx[i] : -INFINITY;
+          for (int iv = 0; iv < 4; ++iv)
+            sv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(kr[h][iv]), as_bf16x8(qv[nb][iv]), sv, 0, 0, 0);
+          const int key0 = jb + 16 * h + 4 * j4;
+          float4 st;
+          st.x = sv[0] * s.scale_log2; st.y = sv[1] * s.scale_log2;
+          st.z = sv[2] * s.scale_log2; st.w = sv[3] * s.scale_log2;
+          if (seg == 1 && rr < nrows) *reinterpret_cast<float4*>(&sm_logit[rr * SKP + (tt - ntp - win * WT) * kTK + 16 * h + 4 * j4]) = st;
+          if (seg == 2) *reinterpret_cast<float4*>(&sm_new[rr][16 * h + 4 * j4]) = st;
+          const float sx[4] = {st.x, st.y, st.z, st.w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int key = key0 + i;
+            // past the segment, or an appended token that comes after this row's own (causal order)
+            const bool ok = key < jn && !(seg == 2 && key - n0 > qi[nb]);
+            x[nb][4 * h + i] = ok ? sx[i] : -INFINITY;
+          }
         }
       }
     };
     // running softmax over the tile's scores; returns the probabilities as the bf16 B operand
-    auto softmax_tile = [&](const float (&x)[8]) __attribute__((always_inline)) {
+    auto softmax_tile = [&](const float (&x)[8], float& m_r, float& l_r, f32x4_t (&ac)[8]) __attribute__((always_inline)) {
       float tm = x[0];
 #pragma unroll
       for (int i = 1; i < 8; ++i) tm = fmaxf(tm, x[i]);
-      if (__any(tm > m_run + kSlack)) {
+      if (__any(tm > m_r + kSlack)) {
         // the four lanes of a row raise the reference together, to the row's maximum over the tile
         tm = fmaxf(tm, __shfl_xor(tm, 16));
         tm = fmaxf(tm, __shfl_xor(tm, 32));
-        if (tm > m_run + kSlack) {
-          const float cf = fast_exp2(m_run - tm);   // exp2(-inf) = 0 on the first raise
-          l_run *= cf;
-          m_run = tm;
+        if (tm > m_r + kSlack) {
+          const float cf = fast_exp2(m_r - tm);   // exp2(-inf) = 0 on the first raise
+          l_r *= cf;
+          m_r = tm;
 #pragma unroll
-          for (int dc = 0; dc < 8; ++dc) acc[dc] *= cf;
+          for (int dc = 0; dc < 8; ++dc) ac[dc] *= cf;
         }
       }
       bf16x8_t pb;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const float p = (x[i] == -INFINITY) ? 0.f : fast_exp2(x[i] - m_run);
-        l_run += p;
+        const float p = (x[i] == -INFINITY) ? 0.f : fast_exp2(x[i] - m_r);
+        l_r += p;
         pb[i] = (__bf16)p;
       }
       return pb;
     };
     // acc += V^T P^T.  V^T operand for chunk dc: element 4h + i = bf16 number dc of the vector of
     // key 4j + i, half h
-    auto value_tile = [&](const uint4 (&vr)[2][4], bf16x8_t pb) __attribute__((always_inline)) {
+    auto value_tile = [&](const uint4 (&vr)[2][4], const bf16x8_t (&pb)[NB]) __attribute__((always_inline)) {
       uint32_t vw[2][4][4];
 #pragma unroll
       for (int h = 0; h < 2; ++h)
@@ -337,7 +357,9 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         av.y = __builtin_amdgcn_perm(vw[0][3][w], vw[0][2][w], sel);
         av.z = __builtin_amdgcn_perm(vw[1][1][w], vw[1][0][w], sel);
         av.w = __builtin_amdgcn_perm(vw[1][3][w], vw[1][2][w], sel);
-        acc[dc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), pb, acc[dc], 0, 0, 0);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+          acc[nb][dc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), pb[nb], acc[nb][dc], 0, 0, 0);
       }
     };
 
@@ -351,10 +373,12 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       load_k(tt, t_hi, kbuf);
       load_v(tt, t_hi, vbuf);
       while (tt < t_hi) {
-        float x[8];
+        float x[NB][8];
         score_tile(tt, kbuf, x);
         load_k(tt + WPB, t_hi, kbuf);
-        const bf16x8_t pb = softmax_tile(x);
+        bf16x8_t pb[NB];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) pb[nb] = softmax_tile(x[nb], m_run[nb], l_run[nb], acc[nb]);
         value_tile(vbuf, pb);
         load_v(tt + WPB, t_hi, vbuf);
         tt += WPB;
@@ -389,48 +413,52 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
       t_lo = t_hi;
     }
-    // the four lanes of a row saw different keys: add up their sums (the accumulators are already
-    // contracted over all keys of the wave)
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
-
-    // waves -> one partial per piece in a single pass: every wave leaves its accumulators,
-    // reference and sum in LDS (lane-major, conflict-free); after one barrier, thread
+    // waves -> one partial per piece, a block of 16 rows at a time: every wave leaves its
+    // accumulators, reference and sum in LDS (lane-major, conflict-free); after one barrier, thread
     // (lane, i, q) merges four consecutive output elements over the waves and stores them.
-    {
-      float (*dst)[64] = sm_part[wave];
 #pragma unroll
-      for (int dc = 0; dc < 8; ++dc)
+    for (int nb = 0; nb < NB; ++nb) {
+      // the four lanes of a row saw different keys: add up their sums (the accumulators are
+      // already contracted over all keys of the wave)
+      float l_row = l_run[nb];
+      l_row += __shfl_xor(l_row, 16);
+      l_row += __shfl_xor(l_row, 32);
+      if (nb > 0) __syncthreads();       // sm_part still holds the previous block
+      {
+        float (*dst)[64] = sm_part[wave];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) dst[dc * 4 + i][lane] = acc[dc][i];
-      dst[32][lane] = m_run;
-      dst[33][lane] = l_run;
-    }
-    __syncthreads();
-    for (int item = tid; item < 64 * 8; item += kThreads) {
-      const int ln = item & 63, iq = item >> 6;       // source lane; (i, q) = (iq & 3, iq >> 2)
-      const int row = ln & 15, jj = ln >> 4, i = iq & 3, q = iq >> 2;
-      if (row < nrows) {
-        float mx = sm_part[0][32][ln];
+        for (int dc = 0; dc < 8; ++dc)
 #pragma unroll
-        for (int w = 1; w < WPB; ++w) mx = fmaxf(mx, sm_part[w][32][ln]);
-        float o[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;
+          for (int i = 0; i < 4; ++i) dst[dc * 4 + i][lane] = acc[nb][dc][i];
+        dst[32][lane] = m_run[nb];
+        dst[33][lane] = l_row;
+      }
+      __syncthreads();
+      for (int item = tid; item < 64 * 8; item += kThreads) {
+        const int ln = item & 63, iq = item >> 6;       // source lane; (i, q) = (iq & 3, iq >> 2)
+        const int row = (ln & 15) + 16 * nb, jj = ln >> 4, i = iq & 3, q = iq >> 2;
+        if (row < nrows) {
+          float mx = sm_part[0][32][ln];
 #pragma unroll
-        for (int w = 0; w < WPB; ++w) {
-          const float mw = sm_part[w][32][ln];
-          // a wave without visible keys has reference -inf; if no wave had any, mx is -inf as well
-          const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - mx);
-          lt = fmaf(e, sm_part[w][33][ln], lt);
+          for (int w = 1; w < WPB; ++w) mx = fmaxf(mx, sm_part[w][32][ln]);
+          float o[4] = {0.f, 0.f, 0.f, 0.f}, lt = 0.f;
 #pragma unroll
-          for (int c = 0; c < 4; ++c) o[c] = fmaf(e, sm_part[w][(4 * q + c) * 4 + i][ln], o[c]);
-        }
-        const size_t slot = (size_t)blockIdx.x + (size_t)b * units + ul;
-        // accumulator (dc, i) of lane (row, jj) is output element 8 * (4 jj + i) + dc
-        *reinterpret_cast<float4*>(a.sc.part_o + (slot * 16 + row) * kD + 8 * (4 * jj + i) + 4 * q) =
-            make_float4(o[0], o[1], o[2], o[3]);
-        if (jj == 0 && iq == 0) {
-          a.sc.part_ml[(slot * 16 + row) * 2] = mx;
-          a.sc.part_ml[(slot * 16 + row) * 2 + 1] = lt;
+          for (int w = 0; w < WPB; ++w) {
+            const float mw = sm_part[w][32][ln];
+            // a wave without visible keys has reference -inf; if no wave had any, mx is -inf as well
+            const float e = (mw == -INFINITY) ? 0.f : fast_exp2(mw - mx);
+            lt = fmaf(e, sm_part[w][33][ln], lt);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) o[c] = fmaf(e, sm_part[w][(4 * q + c) * 4 + i][ln], o[c]);
+          }
+          const size_t slot = (size_t)blockIdx.x + (size_t)b * units + ul;
+          // accumulator (dc, i) of lane (row, jj) is output element 8 * (4 jj + i) + dc
+          *reinterpret_cast<float4*>(a.sc.part_o + (slot * kRows + row) * kD + 8 * (4 * jj + i) + 4 * q) =
+              make_float4(o[0], o[1], o[2], o[3]);
+          if (jj == 0 && iq == 0) {
+            a.sc.part_ml[(slot * kRows + row) * 2] = mx;
+            a.sc.part_ml[(slot * kRows + row) * 2 + 1] = lt;
+          }
         }
       }
     }
@@ -448,6 +476,7 @@ struct FinishMqArgs {
   InlineLens lens;
   float inv_H;
   int R, Q, HP, passes;
+  int RPS;      // rows per partial slot: 16 x row blocks of the attention pass
 };
 
 constexpr int kFinishThreads = 256;
@@ -497,7 +526,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   const int Lb = M + n1;
   const int rows = s.H * Q;
   const int tid = threadIdx.x, lane = tid & 63;
-  constexpr int mlstride = 16 * 2;
+  const int mlstride = a.RPS * 2;
   extern __shared__ float smem[];  // slot blocks: [rows] normalisers + exchange space
 
   const int row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
@@ -508,9 +537,9 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     const int qi = x / s.H, h = x - qi * s.H;
     const RowSpan sp = row_span(a, off_b, b, h, qi, Lb);
     const int ns = sp.ns;
-    const float* ml = a.sc.part_ml + (sp.slot0 * 16 + sp.row) * 2;
-    const float2* po = reinterpret_cast<const float2*>(a.sc.part_o + (sp.slot0 * 16 + sp.row) * kD) + lane;
-    constexpr size_t ostride = (size_t)16 * kD / 2;
+    const float* ml = a.sc.part_ml + (sp.slot0 * a.RPS + sp.row) * 2;
+    const float2* po = reinterpret_cast<const float2*>(a.sc.part_o + (sp.slot0 * a.RPS + sp.row) * kD) + lane;
+    const size_t ostride = (size_t)a.RPS * kD / 2;
     // a row rarely has more than a few pieces: their partial outputs are fetched alongside the
     // (reference, sum) pairs rather than after the weights are known
     constexpr int kPrePieces = 4;
@@ -590,12 +619,12 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       if (on) {
         const int qi = x / s.H;
         const RowSpan sp = row_span(a, off_b, b, x - qi * s.H, qi, Lb);
-        const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * 16 + sp.row);
+        const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * a.RPS + sp.row);
         float m_loc = -INFINITY, l_loc = 0.f;
         for (int i0 = part; i0 < sp.ns; i0 += 4 * parts) {   // four loads in flight
           float2 v[4];
 #pragma unroll
-          for (int k = 0; k < 4; ++k) v[k] = ml[(size_t)min(i0 + k * parts, sp.ns - 1) * 16];
+          for (int k = 0; k < 4; ++k) v[k] = ml[(size_t)min(i0 + k * parts, sp.ns - 1) * a.RPS];
 #pragma unroll
           for (int k = 0; k < 4; ++k) {
             if (i0 + k * parts >= sp.ns) continue;
@@ -722,9 +751,9 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   }
 }
 
-template <int WPB, int AUXK = 0, int AUXV = 0>
+template <int WPB, int AUXK = 0, int AUXV = 0, int NB = 1>
 hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  auto kern = attn_mq_kernel<WPB, AUXK, AUXV>;
+  auto kern = attn_mq_kernel<WPB, AUXK, AUXV, NB>;
   if (occupancy) return hipOccupancyMaxActiveBlocksPerMultiprocessor(occupancy, kern, WPB * 64, 0);
   if (tm) hipExtLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, a);
@@ -732,6 +761,8 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 }
 
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
+  // more than 16 rows (heads x query positions): two row blocks per pass
+  if (mq_row_blocks(a.s.G, a.Q) == 2) return launch_mq_w<8, 0, 2, 2>(a, n_groups, occupancy, st, tm);
   // waves per work-group: variant 17 = 4, default 8 (12 waves at 168 registers: 2 % slower)
   if (a.s.variant == 17) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
   // V loads carry the non-temporal hint, K loads do not (variant 20: neither).  A V row is read
@@ -745,7 +776,11 @@ hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 
 }  // namespace
 
-int mq_heads_per_pass(int G, int q_len) { return G < 16 / q_len ? G : 16 / q_len; }
+int mq_row_blocks(int G, int q_len) { return G * q_len > 16 ? 2 : 1; }
+int mq_heads_per_pass(int G, int q_len) {
+  const int rows = 16 * mq_row_blocks(G, q_len);
+  return G < rows / q_len ? G : rows / q_len;
+}
 
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
@@ -763,6 +798,7 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
   MqArgs a;
   memset(&a, 0, sizeof a);
   a.s = s;
+  a.Q = 1;
   return launch_mq_v(a, 0, out, nullptr, nullptr);
 }
 
@@ -774,6 +810,7 @@ hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& 
   a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
+  a.RPS = 16 * mq_row_blocks(s.G, q_len);
   const int rows = s.H * q_len;
   const bool one = q_len == 1 && s.H <= 32;
   const int slots = one ? kFinishThreads : kSlotsMulti;

@@ -97,7 +97,10 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
                         int threshold, hipStream_t st, const KernelTimer* tm = nullptr);
 
 // Multi-query step (bf16, head_dim 128): q_len query rows per sequence on the matrix cores.
-// A pass serves mq_heads_per_pass(G, q_len) query heads x q_len rows <= 16 rows per KV head.
+// A pass serves mq_heads_per_pass(G, q_len) query heads x q_len rows per KV head, in
+// mq_row_blocks(G, q_len) blocks of 16 rows (two when heads x rows exceed 16); a partial slot holds
+// 16 x blocks rows.
+int mq_row_blocks(int G, int q_len);
 int mq_heads_per_pass(int G, int q_len);
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,

@@ -47,9 +47,13 @@ def _small(G, Hkv, **kw):
     (8, 1, 2),     # exactly 16 rows
     (1, 2, 16),    # no grouping, 16 query positions
     (2, 2, 8),
-    (4, 1, 8),     # two heads per pass, two passes
+    (4, 1, 8),     # 32 rows: two row blocks, one pass
     (3, 2, 5),     # 15 rows
-    (12, 1, 3),    # five heads per pass, three passes, the last with two heads
+    (12, 1, 3),    # 36 rows: ten heads per pass in two row blocks, two passes, the last with two heads
+    (7, 1, 4),     # Qwen grouping, 28 rows in two row blocks
+    (4, 2, 16),    # two heads per pass, two passes of 32 rows
+    (4, 1, 5),     # 20 rows: the second row block has four
+    (20, 1, 1),    # single query, more heads per KV head than one row block holds
 ])
 @pytest.mark.parametrize("split_keys", [0, 64])
 def test_chunked_decode_matches_token_by_token_oracle(mkv, G, Hkv, Q, split_keys):
