@@ -54,6 +54,8 @@ def _small(G, Hkv, **kw):
     (4, 2, 16),    # two heads per pass, two passes of 32 rows
     (4, 1, 5),     # 20 rows: the second row block has four
     (20, 1, 1),    # single query, more heads per KV head than one row block holds
+    (12, 4, 1),    # 48 heads: the finishing kernel's general instantiation with one query row
+    (6, 8, 2),     # 48 heads, two rows
 ])
 @pytest.mark.parametrize("split_keys", [0, 64])
 def test_chunked_decode_matches_token_by_token_oracle(mkv, G, Hkv, Q, split_keys):

@@ -120,12 +120,13 @@ def test_every_kv_head_keeps_its_own_tokens(mkv, G, Hkv, D, dtype, variant):
         ls.close()
 
 
-def test_multi_query_calls(mkv):
-    wl = _wl(4, 2)
-    ls = PerHeadLockstep(mkv, wl, max_q_len=4)
+@pytest.mark.parametrize("G,Hkv,Q", [(4, 2, 4), (4, 2, 8), (7, 2, 4)])   # 16 rows; 32 and 28 rows in two row blocks
+def test_multi_query_calls(mkv, G, Hkv, Q):
+    wl = _wl(G, Hkv)
+    ls = PerHeadLockstep(mkv, wl, max_q_len=Q)
     try:
         t = 0
-        for n in [4, 1, 3, 4, 2, 4, 4, 1, 1, 4, 3, 4, 4, 4, 2, 4, 4, 4]:
+        for n in [Q, 1, 3, Q, 2, Q, Q, 1, 1, Q, 3, Q, Q, Q, 2, Q, Q, Q]:
             ls.feed(t, n)
             t += n
         assert ls.evictions >= 8 and ls.distinct_sets > 1
