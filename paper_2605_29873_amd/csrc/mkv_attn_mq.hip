@@ -312,7 +312,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         }
       }
     };
-    // running softmax over the tile's scores; returns the probabilities as the bf16 B operand
+    struct PairB { bf16x8_t hi, lo; };
+    // running softmax over the tile's scores; returns the probabilities as bf16 B operands
     auto softmax_tile = [&](const float (&x)[8], float& m_r, float& l_r, f32x4_t (&ac)[8]) __attribute__((always_inline)) {
       float tm = x[0];
 #pragma unroll
@@ -329,18 +330,22 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
           for (int dc = 0; dc < 8; ++dc) ac[dc] *= cf;
         }
       }
-      bf16x8_t pb;
+      // the probability enters the value contraction as two bf16 terms, p = hi + lo up to 2^-17:
+      // with hi alone (2^-9) an output over a handful of keys can miss the bf16 tolerance
+      PairB pb;
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const float p = (x[i] == -INFINITY) ? 0.f : fast_exp2(x[i] - m_r);
         l_r += p;
-        pb[i] = (__bf16)p;
+        const __bf16 hi = (__bf16)p;
+        pb.hi[i] = hi;
+        pb.lo[i] = (__bf16)(p - (float)hi);
       }
       return pb;
     };
     // acc += V^T P^T.  V^T operand for chunk dc: element 4h + i = bf16 number dc of the vector of
     // key 4j + i, half h
-    auto value_tile = [&](const uint4 (&vr)[2][4], const bf16x8_t (&pb)[NB]) __attribute__((always_inline)) {
+    auto value_tile = [&](const uint4 (&vr)[2][4], const PairB (&pb)[NB]) __attribute__((always_inline)) {
       uint32_t vw[2][4][4];
 #pragma unroll
       for (int h = 0; h < 2; ++h)
@@ -358,8 +363,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         av.z = __builtin_amdgcn_perm(vw[1][1][w], vw[1][0][w], sel);
         av.w = __builtin_amdgcn_perm(vw[1][3][w], vw[1][2][w], sel);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-          acc[nb][dc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), pb[nb], acc[nb][dc], 0, 0, 0);
+        for (int nb = 0; nb < NB; ++nb) {
+          acc[nb][dc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), pb[nb].hi, acc[nb][dc], 0, 0, 0);
+          acc[nb][dc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(av), pb[nb].lo, acc[nb][dc], 0, 0, 0);
+        }
       }
     };
 
@@ -376,7 +383,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         float x[NB][8];
         score_tile(tt, kbuf, x);
         load_k(tt + WPB, t_hi, kbuf);
-        bf16x8_t pb[NB];
+        PairB pb[NB];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) pb[nb] = softmax_tile(x[nb], m_run[nb], l_run[nb], acc[nb]);
         value_tile(vbuf, pb);

@@ -165,3 +165,27 @@ def test_batch_beyond_the_inline_length_table(mkv):
     ls.prefill()
     _chunks(ls, 36, [3, 1, 2], check_abar=True)
     assert ls.evictions >= 4 * 2
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_shapes_and_call_lengths(mkv, i):
+    # seeded sweep over head groupings (one and two row blocks per pass, several passes), budgets,
+    # chunks, windows and ragged prefills, with calls of mixed lengths; 64-key work-group ranges
+    # cut the units into many pieces at odd places
+    rng = np.random.default_rng(9000 + i)
+    G = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12]))
+    Hkv = int(rng.choice([1, 2, 4]))
+    Q = int(rng.choice([2, 3, 4, 5, 8, 11, 16]))
+    budget = int(rng.integers(Q, 90))
+    chunk = int(rng.integers(1, 40))
+    W = int(rng.integers(0, budget + 1)) if rng.random() < 0.5 else 0
+    M = int(rng.choice([0, 1, 63, 64, 65, 200, 777]))
+    wl = X.Workload(f"randmq{i}", batch=int(rng.integers(1, 5)), n_layers=1, n_q_heads=G * Hkv, n_kv_heads=Hkv,
+                    head_dim=128, dtype="bf16", prefill_min=M // 2, prefill_max=M, decode_budget=budget,
+                    evict_trigger=budget + chunk - 1, recent_window=W, alpha=float(rng.choice([0.2, 0.8, 0.98])),
+                    steps=0, hh_prob=0.05, seed=3000 + i)
+    q_lens = [int(x) for x in rng.integers(0, Q + 1, size=6)] + [Q]
+    ls = Lockstep(mkv, wl, split_keys=int(rng.choice([0, 64, 128])), max_q_len=Q)
+    ls.prefill()
+    tokens = min(wl.evict_trigger + 2 * chunk + Q, 150)
+    _chunks(ls, tokens, q_lens, check_abar=True)
