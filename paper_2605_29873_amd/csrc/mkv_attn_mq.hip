@@ -1,10 +1,10 @@
 // Decode attention on the matrix cores for bf16 layers with 128-wide heads: the single-query step
 // (Q = 1) and the multi-query step (Q <= 16 query rows per sequence and call: chunked or speculative
 // decoding, causal among the Q appended tokens).  With the G query heads that share a KV head, a
-// pass has up to 16 rows (heads x query positions) against every key, so QK^T and PV are 16-wide
-// contractions and run on MFMA; what is left for the vector ALU is the softmax.  Paper: Eq. 2
-// (attention over the prefill and decode pools), Eq. 4-6 (head mean and momentum, applied once per
-// query row in order), Algorithm 1 "append".
+// pass has up to 16 rows (heads x query positions) against every key -- 32, as two row blocks, when
+// G x Q exceeds 16 -- so QK^T and PV are 16-wide contractions and run on MFMA; what is left for
+// the vector ALU is the softmax.  Paper: Eq. 2 (attention over the prefill and decode pools),
+// Eq. 4-6 (head mean and momentum, applied once per query row in order), Algorithm 1 "append".
 //
 // gfx950 only: v_mfma_f32_16x16x32_bf16.  Operand layouts (lane l, r = l % 16, j = l / 16):
 //   A[m][k] : lane holds m = r, k = 8j .. 8j+7      B[k][n] : lane holds n = r, k = 8j .. 8j+7
@@ -87,7 +87,8 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 // operand (lane (r, j) loads the 16-byte vectors 4*iv + j of key r; the queries are loaded the same
 // way, so both operands see the same permutation of the head dimension).  The C layout leaves lane
 // (r, j) with the scores of query row r against keys 4j .. 4j+3 of each tile -- which, rounded to
-// bf16, is exactly the B operand of  O^T = V^T * P^T  with the 32 keys as the contraction index.
+// bf16 (a high and a low part, two MFMAs), is exactly the B operand of  O^T = V^T * P^T  with the
+// 32 keys as the contraction index.
 // The V^T operand wants, per lane, one head-dim element of 8 keys: lane (r, j) loads vector r of
 // the 8 keys it contracts and transposes 16-bit halves in registers (one byte-permute per dword).
 // The accumulators then hold O[row r][8 * (4j + i) + dc] for chunk dc, i = 0..3.
@@ -280,7 +281,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
 
     int win = 0;
     constexpr float kSlack = 8.0f;
-    // scores of one tile against the 16 rows: x[4h + i] = logit of key 16h + 4j + i (base 2), -inf
+    // scores of one tile against the rows of each block: x[nb][4h + i] = logit of key 16h + 4j + i (base 2), -inf
     // where masked; decode logits are staged for the score update
     auto score_tile = [&](int tt, const uint4 (&kr)[2][4], float (&x)[NB][8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
