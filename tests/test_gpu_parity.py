@@ -286,3 +286,18 @@ def test_largest_supported_batch(mkv, dtype, D):
     ls.prefill()
     _run(ls, 12, check_abar=True)
     assert ls.evictions >= 3 * 3
+
+
+@pytest.mark.parametrize("dtype,D,G", [("bf16", 128, 4), ("f32", 64, 2)])
+def test_decode_pool_at_the_largest_capacity(mkv, dtype, D, G):
+    # 16384 decode slots (what the selection kernel holds in LDS): steps that fill the last slots,
+    # then an eviction of 84 tokens out of 16384
+    wl = X.Workload("maxcap", batch=2, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=D, dtype=dtype,
+                    prefill_min=40, prefill_max=90, decode_budget=16300, evict_trigger=16383,
+                    recent_window=100, alpha=0.9, steps=0, hh_prob=0.01)
+    assert wl.capacity == 16384
+    ls = Lockstep(mkv, wl, seqs=[1], active=range(wl.batch))
+    ls.prefill()
+    ls.load_snapshot(16381, 60000)
+    _run(ls, 4, t0=60000, check_abar=True)
+    assert ls.evictions == 1
