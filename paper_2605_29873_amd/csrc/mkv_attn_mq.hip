@@ -771,8 +771,9 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
   // more than 16 rows (heads x query positions): two row blocks per pass
   if (mq_row_blocks(a.s.G, a.Q) == 2) return launch_mq_w<8, 0, 2, 2>(a, n_groups, occupancy, st, tm);
-  // waves per work-group: variant 17 = 4, default 8 (12 waves at 168 registers: 2 % slower)
-  if (a.s.variant == 17) return launch_mq_w<4>(a, n_groups, occupancy, st, tm);
+  // waves per work-group: variant 17 = 4, default 8 (four waves: the Llama-shaped layer 63.8 -> 65.0 us,
+  // the Qwen-shaped one 26.5 -> 27.8 us, the 86 GB context unchanged; 12 waves at 168 registers: 2 % slower)
+  if (a.s.variant == 17) return launch_mq_w<4, 0, 2>(a, n_groups, occupancy, st, tm);
   // V loads carry the non-temporal hint, K loads do not (variant 20: neither).  A V row is read
   // whole by one load instruction and never again in the launch; a K row is read in 64-byte pieces
   // by four instructions, and with the hint its cache lines were sometimes dropped between them
