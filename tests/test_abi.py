@@ -78,3 +78,23 @@ def test_null_arguments(lib):
     assert lib.mkv_destroy(None) == B.MKV_OK
     assert lib.mkv_evict(None, 0, 0) == B.MKV_ERR_ARG
     assert lib.mkv_get_lens(None, 0, 0, None, None, None) == B.MKV_ERR_ARG
+
+
+def test_header_is_plain_c_and_the_binding_mirrors_its_struct(tmp_path):
+    """include/mkv.h compiles as C99 on its own, and the ctypes mirror of mkv_config has the
+    header's size and field offsets (checked with a small C program, no GPU involved)."""
+    import subprocess
+    fields = [name for name, _ in B.mkv_config._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "mkv.h"', 'int main(void) {',
+             '  printf("%zu\\n", sizeof(mkv_config));']
+    lines += [f'  printf("%zu\\n", offsetof(mkv_config, {f}));' for f in fields]
+    lines += ['  return 0;', '}']
+    src.write_text("\n".join(lines) + "\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert int(out[0]) == C.sizeof(B.mkv_config)
+    for f, off in zip(fields, out[1:]):
+        assert int(off) == getattr(B.mkv_config, f).offset, f
