@@ -49,6 +49,22 @@ def test_cfg2_llama_layer_crosses_an_eviction(mkv):
     print(f"cfg2: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
 
 
+def test_cfg2_full_run_lockstep(mkv):
+    # the whole run of the batch-1 Llama-shaped layer: 4096 steps from an empty decode pool, all
+    # eight bursts, 48 evictions of 64 tokens, every step compared (about a minute, the oracle's)
+    wl = WL["cfg2"]
+    ls = Lockstep(mkv, wl)
+    ls.prefill()
+    try:
+        for t in range(wl.steps):
+            ls.step(t, check_abar=(t % 16 == 0))
+        ls.check_prefill_untouched(0)
+    finally:
+        ls.close()
+    assert ls.evictions == 48          # first at step 1088, then every 64 steps
+    print(f"cfg2 full run: max |out err| {ls.max_out_err:.2e}, max score rel {ls.max_score_rel:.2e}")
+
+
 def test_cfg2_burst_window_from_empty_pool(mkv):
     # the first 140 steps of the real run, short prefill to keep the oracle quick
     wl = X.scaled(WL["cfg2"], prefill_min=700, prefill_max=700, decode_budget=96, evict_trigger=96 + 15,
