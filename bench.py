@@ -174,6 +174,7 @@ def algorithmic_bytes(job: Job, n_d_before: list[int]):
         attn += nq * wl.n_q_heads * wl.head_dim * b       # q read
         attn += nq * row                                  # append write
         rest += nq * wl.n_q_heads * wl.head_dim * b       # out write
+        rest += nq * n1 * wl.n_kv_heads * 4 * 2           # decode-slice probabilities per KV group, write + read
         rest += n1 * 4 * 2                                # I read + write
     return attn + rest, attn
 
