@@ -57,6 +57,7 @@ struct MqArgs {
   int Q;        // query rows per sequence
   int HP;       // query heads served per pass: min(G, rows per pass / Q)
   int passes;   // passes per KV head: ceil(G / HP)
+  int P;        // positions of the flattened axis that stand for the fixed cost of starting a piece
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   __shared__ float sm_logit[kWindow + kRows * 4];   // rows of SK + 4 floats (the pad spreads the banks)
   __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
   __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q, offs, lane, &a.lens);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + a.P, offs, lane, &a.lens);
   __syncthreads();
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -148,11 +149,21 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int n0 = uniform(a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b]);
     const int n1 = n0 + Q;
     const int L = M + n1;
-    const int ul = uniform((int)((r0 - ob) / L));   // (the 64-bit division runs on the vector ALU)
+    // On the flattened axis a unit is P positions longer than its L keys: the first P positions
+    // stand for what starting a piece costs (prologue, merge), so that a work-group whose range
+    // crosses a unit boundary gets that many keys fewer.  A range that ends inside them has no keys
+    // of the unit and leaves no partial.
+    const int Lp = L + a.P;
+    const int ul = uniform((int)((r0 - ob) / Lp));   // (the 64-bit division runs on the vector ALU)
     const int g = ul / a.passes;
     const int pass = ul - g * a.passes;
-    const int ka = uniform((int)(r0 - ob - (long long)ul * L));
-    const int ke = uniform((int)min((long long)L, ka + (r1 - r0)));
+    const int kav = uniform((int)(r0 - ob - (long long)ul * Lp));
+    const int kev = uniform((int)min((long long)Lp, kav + (r1 - r0)));
+    const int ka = max(kav - a.P, 0), ke = max(kev - a.P, 0);
+    if (ke <= ka) {
+      r0 += kev - kav;
+      continue;
+    }
     const int p0 = min(ka, M), p1 = min(ke, M);
     const int d0 = max(ka, M) - M, d1 = max(ke, M) - M;
     // three kinds of tiles: prefill keys [p0, p1); decode keys that are in the pool already
@@ -471,7 +482,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       }
     }
     __syncthreads();   // sm_part is reused by the next piece
-    r0 += ke - ka;
+    r0 += kev - kav;
   }
 }
 
@@ -485,6 +496,7 @@ struct FinishMqArgs {
   float inv_H;
   int R, Q, HP, passes;
   int RPS;      // rows per partial slot: 16 x row blocks of the attention pass
+  int P;        // as in the attention kernel
 };
 
 constexpr int kFinishThreads = 256;
@@ -499,7 +511,7 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / a.HP;
   const int ul = g * a.passes + pass;
-  const long long off_u = off_b + (long long)ul * L;
+  const long long off_u = off_b + (long long)ul * (L + a.P) + a.P;   // the unit's first key on the flattened axis
   const long long kf = off_u / a.R, kl = (off_u + L - 1) / a.R;
   RowSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * a.passes + ul;
@@ -793,11 +805,11 @@ int mq_heads_per_pass(int G, int q_len) {
 
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
-                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm) {
+                          int keys_per_group, int piece_pad, int n_groups, hipStream_t st, const KernelTimer* tm) {
   MqArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.lens = lens;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
-  a.mask = mask; a.R = keys_per_group; a.Q = q_len;
+  a.mask = mask; a.R = keys_per_group; a.Q = q_len; a.P = piece_pad;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   return launch_mq_v(a, n_groups, nullptr, st, tm);
@@ -813,10 +825,10 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
 
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
-                            hipStream_t st, const KernelTimer* tm) {
+                            int piece_pad, hipStream_t st, const KernelTimer* tm) {
   FinishMqArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.lens = lens; a.inv_H = 1.0f / (float)s.H;
-  a.R = keys_per_group; a.Q = q_len;
+  a.R = keys_per_group; a.Q = q_len; a.P = piece_pad;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   a.RPS = 16 * mq_row_blocks(s.G, q_len);
