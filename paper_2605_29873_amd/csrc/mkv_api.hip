@@ -329,8 +329,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     const int hp = mq_heads_per_pass(G, q_len);
     passes = (G + hp - 1) / hp;
   }
-  // positions per unit that stand for the fixed cost of a piece (matrix-core kernels only)
-  const int P = mq ? kPiecePad : 0;
+  const int P = c->shape.piece_pad;   // positions per unit that stand for the fixed cost of a piece
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
   InlineLens lens;
@@ -390,10 +389,10 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
   hipError_t e;
-  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, P, n_groups, c->stream, pe ? &t_attn : nullptr);
+  if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
-  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, P, c->stream, pe ? &t_fin : nullptr);
+  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   else e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "finish launch");
   for (int b = 0; b < B; ++b) {
@@ -467,6 +466,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   s.budget = cfg->decode_budget; s.window = cfg->recent_window; s.alpha = cfg->alpha;
   s.trigger = cfg->evict_trigger; s.S = c->lay.S;
   s.variant = cfg->attn_variant;
+  s.piece_pad = kPiecePad;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
   s.scale_log2 = (float)(scale * 1.4426950408889634074);
   const size_t LB = (size_t)cfg->n_layers * cfg->batch;

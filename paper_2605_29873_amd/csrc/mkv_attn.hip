@@ -121,7 +121,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   constexpr int WT = 6144 / (HL * TK);   // decode tiles per logit staging window (24 KiB of LDS)
   constexpr int SK = WT * TK;            // keys per window
   __shared__ float sm_logit[HL][SK];
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1, offs, lane);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1 + s.piece_pad, offs, lane);
   __syncthreads();
   if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -163,11 +163,22 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     const int n0 = a.lv.nd[b];
     const int n1 = n0 + 1;              // the pool the softmax sees includes the token appended now
     const int L = M + n1;
-    const int ul = (int)((r0 - offs[b]) / L);           // unit inside the sequence
+    // On the flattened axis a unit is piece_pad positions longer than its L keys: the first ones
+    // stand for what starting a piece costs, so that a work-group whose range crosses a unit
+    // boundary gets that many keys fewer.  A range that ends inside them has no keys of the unit
+    // and leaves no partial.
+    const int Lp = L + s.piece_pad;
+    const int ul = (int)((r0 - offs[b]) / Lp);          // unit inside the sequence
     const int g = ul / s.passes;
     const int pass = ul - g * s.passes;
-    const int ka = (int)(r0 - offs[b] - (long long)ul * L);   // first key of the piece in the unit
-    const int ke = (int)min((long long)L, ka + (r1 - r0));     // one past its last key
+    const int kav = (int)(r0 - offs[b] - (long long)ul * Lp);
+    const int kev = (int)min((long long)Lp, kav + (r1 - r0));
+    const int ka = max(kav - s.piece_pad, 0);           // first key of the piece in the unit
+    const int ke = max(kev - s.piece_pad, 0);           // one past its last key
+    if (ke <= ka) {
+      r0 += kev - kav;
+      continue;
+    }
     // the piece as two sub-ranges: prefill keys [p0, p1), decode slots [d0, d1)
     const int p0 = min(ka, M), p1 = min(ke, M);
     const int d0 = max(ka, M) - M, d1 = max(ke, M) - M;
@@ -488,7 +499,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
       }
     }
     __syncthreads();  // the LDS staging is reused by the next piece
-    r0 += ke - ka;
+    r0 += kev - kav;
   }
 }
 
@@ -511,7 +522,8 @@ __device__ __forceinline__ PieceSpan piece_span(const Shape& s, const long long*
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / s.HL;
   const int ul = g * s.passes + pass;
-  const long long off_u = offs[b] + (long long)ul * L;
+  // a unit takes L + piece_pad positions of the flattened axis, its keys after the pad
+  const long long off_u = offs[b] + (long long)ul * (L + s.piece_pad) + s.piece_pad;
   const long long kf = off_u / R, kl = (off_u + L - 1) / R;
   PieceSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * s.passes + ul;

@@ -57,7 +57,6 @@ struct MqArgs {
   int Q;        // query rows per sequence
   int HP;       // query heads served per pass: min(G, rows per pass / Q)
   int passes;   // passes per KV head: ceil(G / HP)
-  int P;        // positions of the flattened axis that stand for the fixed cost of starting a piece
 };
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& v) { return __builtin_bit_cast(bf16x8_t, v); }
@@ -115,7 +114,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   __shared__ float sm_logit[kWindow + kRows * 4];   // rows of SK + 4 floats (the pad spreads the banks)
   __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
   __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + a.P, offs, lane, &a.lens);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + s.piece_pad, offs, lane, &a.lens);
   __syncthreads();
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -153,13 +152,13 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // stand for what starting a piece costs (prologue, merge), so that a work-group whose range
     // crosses a unit boundary gets that many keys fewer.  A range that ends inside them has no keys
     // of the unit and leaves no partial.
-    const int Lp = L + a.P;
+    const int Lp = L + s.piece_pad;
     const int ul = uniform((int)((r0 - ob) / Lp));   // (the 64-bit division runs on the vector ALU)
     const int g = ul / a.passes;
     const int pass = ul - g * a.passes;
     const int kav = uniform((int)(r0 - ob - (long long)ul * Lp));
     const int kev = uniform((int)min((long long)Lp, kav + (r1 - r0)));
-    const int ka = max(kav - a.P, 0), ke = max(kev - a.P, 0);
+    const int ka = max(kav - s.piece_pad, 0), ke = max(kev - s.piece_pad, 0);
     if (ke <= ka) {
       r0 += kev - kav;
       continue;
@@ -496,7 +495,6 @@ struct FinishMqArgs {
   float inv_H;
   int R, Q, HP, passes;
   int RPS;      // rows per partial slot: 16 x row blocks of the attention pass
-  int P;        // as in the attention kernel
 };
 
 constexpr int kFinishThreads = 256;
@@ -511,7 +509,7 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / a.HP;
   const int ul = g * a.passes + pass;
-  const long long off_u = off_b + (long long)ul * (L + a.P) + a.P;   // the unit's first key on the flattened axis
+  const long long off_u = off_b + (long long)ul * (L + s.piece_pad) + s.piece_pad;   // the unit's first key on the flattened axis
   const long long kf = off_u / a.R, kl = (off_u + L - 1) / a.R;
   RowSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * a.passes + ul;
@@ -805,11 +803,11 @@ int mq_heads_per_pass(int G, int q_len) {
 
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
-                          int keys_per_group, int piece_pad, int n_groups, hipStream_t st, const KernelTimer* tm) {
+                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm) {
   MqArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.lens = lens;
   a.q = (const char*)q; a.k_new = (const char*)k_new; a.v_new = (const char*)v_new;
-  a.mask = mask; a.R = keys_per_group; a.Q = q_len; a.P = piece_pad;
+  a.mask = mask; a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   return launch_mq_v(a, n_groups, nullptr, st, tm);
@@ -825,10 +823,10 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
 
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
-                            int piece_pad, hipStream_t st, const KernelTimer* tm) {
+                            hipStream_t st, const KernelTimer* tm) {
   FinishMqArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.lens = lens; a.inv_H = 1.0f / (float)s.H;
-  a.R = keys_per_group; a.Q = q_len; a.P = piece_pad;
+  a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   a.RPS = 16 * mq_row_blocks(s.G, q_len);

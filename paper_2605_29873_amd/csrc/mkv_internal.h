@@ -40,6 +40,7 @@ struct Shape {
   int budget, window;
   int trigger;       // the decode step evicts when the pool exceeds this (INT32_MAX: never)
   int variant;       // attention kernel variant (tuning), 0 = default
+  int piece_pad;     // positions of the flattened key axis charged to a unit for starting a piece
   float alpha;
   float scale_log2;  // softmax scale * log2(e): logits are kept in base-2 units
 };
@@ -104,12 +105,11 @@ int mq_row_blocks(int G, int q_len);
 int mq_heads_per_pass(int G, int q_len);
 hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, const void* q,
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
-                          int keys_per_group, int piece_pad, int n_groups, hipStream_t st,
-                          const KernelTimer* tm = nullptr);
+                          int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
-                            int piece_pad, hipStream_t st, const KernelTimer* tm = nullptr);
+                            hipStream_t st, const KernelTimer* tm = nullptr);
 
 // One-token eviction of the sequences whose evict_key is set, all of which hold budget + 1 tokens:
 // the selection was made by the finishing kernel, this only closes the gap.
