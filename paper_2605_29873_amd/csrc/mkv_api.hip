@@ -380,11 +380,14 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
   }
   // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
-  // the caller fixed the range length
-  auto round64 = [](long long x) { return (x + 63) / 64 * 64; };
+  // the caller fixed the range length.  The length is not rounded: with sequences of equal length
+  // and a unit count that divides (or is divided by) the work-group count, every range then starts
+  // and ends on unit boundaries and no work-group pays for two pieces (the 86 GB context, 256
+  // units on 256 work-groups: 419 -> 406 us per layer); a range may start and end at any key.
   const int target = mq ? c->mq_target_groups : c->target_groups;
-  long long R = c->cfg.split_keys ? c->cfg.split_keys : round64((total_keys + target - 1) / target);
-  const long long r_min = round64((total_keys + c->lay.max_groups - 1) / c->lay.max_groups);
+  long long R = c->cfg.split_keys ? c->cfg.split_keys : (total_keys + target - 1) / target;
+  if (R < 64) R = 64;       // a work-group takes at least 64 positions (sizes the partial buffers)
+  const long long r_min = (total_keys + c->lay.max_groups - 1) / c->lay.max_groups;
   if (R < r_min) R = r_min;
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
