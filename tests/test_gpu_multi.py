@@ -167,7 +167,7 @@ def test_batch_beyond_the_inline_length_table(mkv):
     assert ls.evictions >= 4 * 2
 
 
-@pytest.mark.parametrize("i", range(10))
+@pytest.mark.parametrize("i", range(24))
 def test_random_shapes_and_call_lengths(mkv, i):
     # seeded sweep over head groupings (one and two row blocks per pass, several passes), budgets,
     # chunks, windows and ragged prefills, with calls of mixed lengths; 64-key work-group ranges

@@ -226,7 +226,7 @@ def _random_workload(rng, i):
                       steps=0, hh_prob=0.05, seed=1000 + i)
 
 
-@pytest.mark.parametrize("i", range(12))
+@pytest.mark.parametrize("i", range(24))
 def test_random_shapes_lockstep(mkv, i):
     # seeded sweep over head groupings, dims, dtypes, budgets, chunks, windows and ragged prefills,
     # with 64-key work-group ranges so that units are cut into many pieces at odd places
