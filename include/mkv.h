@@ -75,7 +75,7 @@ typedef struct {
                               is also the least allowed.  Required (> B_d) with MKV_NEVER_EVICT.
                               At most 16384                                                     */
   int32_t recent_window;   /* W <= B_d: the W newest decode tokens are never evicted.  0 is the
-                              paper ("regardless of position or recency")                       */
+                              paper: Eq. 8 takes its candidates from the whole decode pool      */
   float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
   float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
   int32_t score_mode;      /* mkv_score_mode                                                     */
@@ -112,7 +112,7 @@ int mkv_destroy(mkv_ctx* ctx);
  * the prompt's K_P, V_P written to the prefill pool.  k, v: device pointers
  * [n_tokens, n_kv_heads, head_dim] in the storage dtype; copied, the caller keeps them.
  * Repeatable until that sequence's first decode step; afterwards MKV_ERR_FROZEN (the prefill pool
- * "is retained in full and never evicted").  MKV_ERR_CAPACITY beyond max_prefill. */
+ * is frozen: "Cache Architecture", Eq. 3 counts it in full).  MKV_ERR_CAPACITY beyond max_prefill. */
 int mkv_prefill_append(mkv_ctx* ctx, int layer, int seq, const void* k, const void* v, int n_tokens);
 
 /* Prompt compression before decoding starts ("Integration of Moment-KV with Prefill Compression

@@ -21,7 +21,7 @@ Readings taken where the paper is silent or ambiguous (each also listed in the d
   R5  eviction cadence generalised: evict iff n_d > T_e, back to exactly B_d.  T_e = B_d is the
       paper (one token per step once full).
   R6  optional recent window W: the W newest decode tokens are not candidates.  W = 0 is the
-      paper ("regardless of position or recency").
+      paper: Eq. 8 draws its candidates from the whole decode pool, with no recency term.
   R7  Eq. 8 leaves ties open (any minimal-sum subset); one choice is pinned: lower score first,
       equal scores -> the older token (smaller original position) goes first.
   R8  removal is stable: survivors keep their order of generation.
@@ -33,6 +33,10 @@ Readings taken where the paper is silent or ambiguous (each also listed in the d
       to the model.  project_kv() states the usual choice for the models the paper runs: linear
       maps k = W_k x, v = W_v x and a rotary encoding of k in the rotate-half layout -- feature i
       of a head pairs with feature i + D/2, angle pos * theta^(-2i/D).
+  R12 the paper fixes no precision.  Everything is fp64 by default; `accumulate=np.float32` on
+      attention_weights / attention_output (and on MomentKVState) takes the same steps with every
+      product, sum and exponential in float32 -- the device's accumulation width -- so that a test
+      can say how much of a device-vs-oracle gap is rounding.  Same code, other dtype.
 
 Pins: tests/test_oracle_*.py (closed forms, invariants, a library SDPA, exhaustive subset
 search).  The multi-step trajectory as a whole is "parity unpinned" against any published
@@ -72,31 +76,33 @@ def project_kv(x: np.ndarray, Wk: np.ndarray, Wv: np.ndarray, pos: int, theta: f
 # Eq. 2: attention of one query over the pool
 # ----------------------------------------------------------------------------------------------
 
-def attention_weights(q: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
+def attention_weights(q: np.ndarray, K: np.ndarray, scale: float, accumulate=np.float64) -> np.ndarray:
     """A[h, j] = softmax_j(scale * <q[h], K[j, h // G]>)  (Eq. 2; Alg. 1 softmax line).
 
-    q [H, D]; K [N, Hkv, D] (pool order: prefill tokens first, then decode tokens); fp64.
+    q [H, D]; K [N, Hkv, D] (pool order: prefill tokens first, then decode tokens).
+    accumulate: dtype of every product, sum and exponential (R12); fp64 unless asked otherwise.
     """
-    q = np.asarray(q, dtype=np.float64)
-    K = np.asarray(K, dtype=np.float64)
+    q = np.asarray(q, dtype=accumulate)
+    K = np.asarray(K, dtype=accumulate)
     H, D = q.shape
     N, Hkv, _ = K.shape
     G = H // Hkv
-    A = np.empty((H, N), dtype=np.float64)
+    A = np.empty((H, N), dtype=accumulate)
     for h in range(H):
-        s = scale * (K[:, h // G, :] @ q[h])          # logits over the whole pool
+        s = accumulate(scale) * (K[:, h // G, :] @ q[h])          # logits over the whole pool
         e = np.exp(s - s.max())
-        A[h] = e / e.sum()
+        A[h] = e / e.sum(dtype=accumulate)
     return A
 
 
-def attention_output(A: np.ndarray, V: np.ndarray) -> np.ndarray:
+def attention_output(A: np.ndarray, V: np.ndarray, accumulate=np.float64) -> np.ndarray:
     """Att[h] = sum_j A[h, j] * V[j, h // G]  (Eq. 2).  A [H, N]; V [N, Hkv, D] -> [H, D]."""
-    V = np.asarray(V, dtype=np.float64)
+    A = np.asarray(A, dtype=accumulate)
+    V = np.asarray(V, dtype=accumulate)
     H, N = A.shape
     Hkv = V.shape[1]
     G = H // Hkv
-    out = np.empty((H, V.shape[2]), dtype=np.float64)
+    out = np.empty((H, V.shape[2]), dtype=accumulate)
     for h in range(H):
         out[h] = A[h] @ V[:, h // G, :]
     return out
@@ -159,7 +165,7 @@ class MomentKVState:
     def __init__(self, n_q_heads: int, n_kv_heads: int, head_dim: int, decode_budget: int,
                  alpha: float, evict_trigger: int | None = None, recent_window: int = 0,
                  softmax_scale: float | None = None, score_mode: str = "layer_mean",
-                 decision_dtype=np.float32):
+                 decision_dtype=np.float32, accumulate=np.float64):
         assert n_q_heads % n_kv_heads == 0
         self.H, self.Hkv, self.D = n_q_heads, n_kv_heads, head_dim
         self.G = n_q_heads // n_kv_heads
@@ -170,6 +176,7 @@ class MomentKVState:
         self.scale = 1.0 / np.sqrt(head_dim) if softmax_scale is None else float(softmax_scale)  # R1
         self.score_mode = score_mode
         self.decision_dtype = decision_dtype                                        # R9
+        self.accumulate = accumulate                                                # R12
         self.Kp = np.zeros((0, n_kv_heads, head_dim))
         self.Vp = np.zeros((0, n_kv_heads, head_dim))
         self.frozen = False
@@ -233,8 +240,8 @@ class MomentKVState:
             # pool <- prefill U decode;  A <- softmax(q K^T / sqrt(d));  Att = A V
             K = np.concatenate([self.Kp, self.Kd[0]])
             V = np.concatenate([self.Vp, self.Vd[0]])
-            A = attention_weights(q, K, self.scale)
-            out = attention_output(A, V)
+            A = attention_weights(q, K, self.scale, self.accumulate)
+            out = attention_output(A, V, self.accumulate)
             # Abar <- mean over heads;  a_dec <- Abar[|prefill|:]
             abar = head_mean(A)[M:]
             # I_i(t) <- alpha I_i(t-1) + abar_i(t) for every decode token (new one included)
@@ -247,8 +254,8 @@ class MomentKVState:
                 K = np.concatenate([self.Kp[:, g:g + 1], self.Kd[g]])
                 V = np.concatenate([self.Vp[:, g:g + 1], self.Vd[g]])
                 qg = q[g * self.G:(g + 1) * self.G]
-                A = attention_weights(qg, K, self.scale)
-                out[g * self.G:(g + 1) * self.G] = attention_output(A, V)
+                A = attention_weights(qg, K, self.scale, self.accumulate)
+                out[g * self.G:(g + 1) * self.G] = attention_output(A, V, self.accumulate)
                 abar = head_mean(A)[M:]
                 self.I[g] = momentum_update(self.I[g], abar, self.alpha)
                 abar_ret.append(abar)
@@ -266,10 +273,16 @@ class MomentKVState:
                 self.last_evicted[v] = np.empty(0, dtype=np.int64)
                 continue
             decision_scores = self.I[v].astype(self.decision_dtype)
-            E = select_evict(decision_scores, self.pos[v], ov, self.window)
-            keep = survivors(n, E)
-            self.last_evicted[v] = self.pos[v][E]
-            self.Kd[v] = self.Kd[v][keep]
-            self.Vd[v] = self.Vd[v][keep]
-            self.I[v] = self.I[v][keep]
-            self.pos[v] = self.pos[v][keep]
+            self.remove(v, select_evict(decision_scores, self.pos[v], ov, self.window))
+
+    def remove(self, v: int, evicted: np.ndarray) -> None:
+        """Eq. 9 for score vector v: the given slots leave, the survivors keep their order (R8).
+        evict() calls it with its own selection; a test whose two sides split on a near-tie
+        calls it with the other side's (checked) selection so that the runs stay comparable."""
+        E = np.asarray(evicted, dtype=np.int64)
+        keep = survivors(self.I[v].shape[0], E)
+        self.last_evicted[v] = self.pos[v][E]
+        self.Kd[v] = self.Kd[v][keep]
+        self.Vd[v] = self.Vd[v][keep]
+        self.I[v] = self.I[v][keep]
+        self.pos[v] = self.pos[v][keep]

@@ -123,3 +123,39 @@ def test_kv_footprint_arithmetic_from_paper():
     assert per_token == kb * 1024
     assert per_token // layers == 4096                                # bytes/token/layer used by bench
     assert round(per_token * tokens / 1e9) == gb
+
+
+@pytest.mark.parametrize("H,Hkv,D,N", [(8, 2, 64, 330), (28, 4, 128, 97), (32, 8, 128, 2048)])
+def test_float32_accumulation_switch_stays_close_to_the_library_sdpa(H, Hkv, D, N):
+    # the rounding probe: same steps in float32.  Pinned to the same library routine as the fp64
+    # path (torch's fp64 SDPA), within what float32 sums over N keys allow, and really float32
+    q, K, V = _rand((H, D), 20), _rand((N, Hkv, D), 21), _rand((N, Hkv, D), 22)
+    G = H // Hkv
+    tq = torch.from_numpy(q)[None, :, None, :]
+    tk = torch.from_numpy(K).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    tv = torch.from_numpy(V).permute(1, 0, 2).repeat_interleave(G, 0)[None]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv)[0, :, 0, :].numpy()
+    A32 = O.attention_weights(q, K, 1 / math.sqrt(D), accumulate=np.float32)
+    out32 = O.attention_output(A32, V, accumulate=np.float32)
+    assert A32.dtype == np.float32 and out32.dtype == np.float32
+    assert np.allclose(out32, ref, rtol=0, atol=1e-5)
+    A64 = O.attention_weights(q, K, 1 / math.sqrt(D))
+    assert np.allclose(A32, A64, rtol=1e-4, atol=1e-9)
+    assert np.any(A32.astype(np.float64) != A64)          # the switch does change the arithmetic
+    assert abs(float(A32.sum(axis=1, dtype=np.float64).max()) - 1.0) < 1e-5
+
+
+def test_float32_accumulation_reaches_the_state_machine():
+    rng = np.random.default_rng(23)
+    a = O.MomentKVState(8, 2, 16, decode_budget=6, alpha=0.9)
+    b = O.MomentKVState(8, 2, 16, decode_budget=6, alpha=0.9, accumulate=np.float32)
+    Kp, Vp = rng.standard_normal((40, 2, 16)), rng.standard_normal((40, 2, 16))
+    a.prefill_append(Kp, Vp); b.prefill_append(Kp, Vp)
+    for t in range(12):
+        q, k, v = rng.standard_normal((8, 16)), rng.standard_normal((2, 16)), rng.standard_normal((2, 16))
+        oa, _ = a.decode_step(q, k, v)
+        ob, _ = b.decode_step(q, k, v)
+        assert ob.dtype == np.float32
+        assert np.allclose(oa, ob, rtol=0, atol=1e-5)
+    assert np.array_equal(a.pos[0], b.pos[0])
+    assert np.allclose(a.I[0], b.I[0], rtol=1e-4)

@@ -172,3 +172,27 @@ def test_decision_precision_is_the_callers():
     st.load_decode(np.zeros((2, 1, 2)), np.zeros((2, 1, 2)), scores=[1.0 + 1e-12, 1.0], pos=[3, 4], t=5)
     st.evict()
     assert st.pos[0].tolist() == [3]
+
+
+def test_remove_takes_exactly_the_given_slots_and_keeps_order():
+    # Eq. 9 on a selection handed in: rows, scores and positions of the named slots leave together
+    rng = np.random.default_rng(31)
+    st = O.MomentKVState(4, 2, 8, decode_budget=5, alpha=0.5, evict_trigger=100)
+    for t in range(9):
+        st.decode_step(rng.standard_normal((4, 8)), rng.standard_normal((2, 8)), rng.standard_normal((2, 8)))
+    K0, V0, I0, p0 = st.Kd[0].copy(), st.Vd[0].copy(), st.I[0].copy(), st.pos[0].copy()
+    st.remove(0, np.array([1, 4, 8]))
+    keep = [0, 2, 3, 5, 6, 7]
+    assert st.pos[0].tolist() == p0[keep].tolist() == keep
+    assert np.array_equal(st.I[0], I0[keep])
+    assert np.array_equal(st.Kd[0], K0[keep]) and np.array_equal(st.Vd[0], V0[keep])
+    assert st.last_evicted[0].tolist() == [1, 4, 8]
+    # evict() is remove() of its own selection
+    a = O.MomentKVState(4, 2, 8, decode_budget=3, alpha=0.5, evict_trigger=100)
+    b = O.MomentKVState(4, 2, 8, decode_budget=3, alpha=0.5, evict_trigger=100)
+    for t in range(7):
+        x = (rng.standard_normal((4, 8)), rng.standard_normal((2, 8)), rng.standard_normal((2, 8)))
+        a.decode_step(*x); b.decode_step(*x)
+    a.evict()
+    b.remove(0, O.select_evict(b.I[0].astype(np.float32), b.pos[0], 4, 0))
+    assert np.array_equal(a.pos[0], b.pos[0]) and np.array_equal(a.I[0], b.I[0])
