@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    config.addinivalue_line("markers", "slow: a GPU case that follows a workload for thousands of steps (minutes, "
+                                       "mostly the CPU oracle's); still part of -m gpu")
 
 
 @pytest.fixture(scope="session")

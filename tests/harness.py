@@ -31,7 +31,8 @@ def from_device(t: torch.Tensor) -> np.ndarray:
 
 def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = None,
              split_keys: int = 0, max_prefill: int | None = None, stream: int | None = None,
-             max_q_len: int = 0, attn_variant: int = 0, score_mode: int = 0):
+             max_q_len: int = 0, attn_variant: int = 0, score_mode: int = 0,
+             decode_capacity: int | None = None):
     cfg = mkv.make_config(
         n_layers=wl.n_layers if layers is None else layers, batch=wl.batch,
         n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads, head_dim=wl.head_dim,
@@ -39,16 +40,81 @@ def make_ctx(mkv, wl: X.Workload, *, manual_evict: bool, layers: int | None = No
         max_prefill=wl.prefill_max if max_prefill is None else max_prefill,
         decode_budget=wl.decode_budget,
         evict_trigger=mkv.MKV_NEVER_EVICT if manual_evict else wl.evict_trigger,
-        decode_capacity=wl.capacity + max(0, max_q_len - 1), recent_window=wl.recent_window,
+        decode_capacity=(wl.capacity + max(0, max_q_len - 1)) if decode_capacity is None else decode_capacity,
+        recent_window=wl.recent_window,
         alpha=wl.alpha, softmax_scale=0.0, score_mode=score_mode,
         split_keys=split_keys, max_q_len=max_q_len, attn_variant=attn_variant,
         stream=stream if stream is not None else torch.cuda.current_stream().cuda_stream)
     return mkv.mkv_create(cfg)
 
 
-def oracle_state(wl: X.Workload) -> O.MomentKVState:
+def oracle_state(wl: X.Workload, score_mode: str = "layer_mean") -> O.MomentKVState:
     return O.MomentKVState(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.decode_budget, wl.alpha,
-                           wl.evict_trigger, wl.recent_window, decision_dtype=np.float32)
+                           wl.evict_trigger, wl.recent_window, score_mode=score_mode,
+                           decision_dtype=np.float32)
+
+
+def oracle_from_gpu(mkv, ctx, wl: X.Workload, layer: int, s: int, per_head: bool = False) -> O.MomentKVState:
+    """An oracle state that starts from what the device holds for (layer, s) right now: both pools
+    (every KV head), the score vector(s), the positions and the step counter, read back through
+    the ABI.  Used for windows that begin in the middle of a device run; from there on the oracle
+    computes everything itself."""
+    st = oracle_state(wl, "per_kv_head" if per_head else "layer_mean")
+    dt = mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32
+    pre = [mkv.mkv_read_kv(ctx, layer, s, 1, g, wl.head_dim, dt) for g in range(wl.n_kv_heads)]
+    dec = [mkv.mkv_read_kv(ctx, layer, s, 0, g, wl.head_dim, dt) for g in range(wl.n_kv_heads)]
+    val = lambda a: storage_to_values(a, wl.dtype).astype(np.float64)
+    st.Kp = np.stack([val(k) for k, _ in pre], axis=1)
+    st.Vp = np.stack([val(v) for _, v in pre], axis=1)
+    if per_head:
+        for g in range(wl.n_kv_heads):
+            mkv.mkv_set_score_view(ctx, g)
+            sc, pos = mkv.mkv_read_scores(ctx, layer, s)
+            st.Kd[g], st.Vd[g] = val(dec[g][0])[:, None, :], val(dec[g][1])[:, None, :]
+            st.I[g], st.pos[g] = sc.astype(np.float64), pos.astype(np.int64)
+        mkv.mkv_set_score_view(ctx, 0)
+    else:
+        sc, pos = mkv.mkv_read_scores(ctx, layer, s)
+        st.Kd[0] = np.stack([val(k) for k, _ in dec], axis=1)
+        st.Vd[0] = np.stack([val(v) for _, v in dec], axis=1)
+        st.I[0], st.pos[0] = sc.astype(np.float64), pos.astype(np.int64)
+    st.t = mkv.mkv_get_lens(ctx, layer, s)[2]
+    st.frozen = True
+    return st
+
+
+class RoundingProbe:
+    """How much of the device-vs-oracle gap of an attention output is float32 rounding: at sampled
+    steps the oracle's attention is taken again with float32 accumulation (same steps, other
+    dtype) over the very pool the step saw, and rounded to the storage dtype like the device's
+    output.  Keeps the step with the largest device gap."""
+
+    def __init__(self, wl: X.Workload):
+        self.wl = wl
+        self.worst = None
+
+    def look(self, st: O.MomentKVState, q, got, ref, t, s):
+        gap = np.abs(got - ref)
+        i = np.unravel_index(np.argmax(gap), gap.shape)
+        if self.worst is not None and gap[i] <= self.worst["device_gap"]:
+            return
+        K = np.concatenate([st.Kp, st.Kd[0]])
+        V = np.concatenate([st.Vp, st.Vd[0]])
+        A32 = O.attention_weights(q, K, st.scale, accumulate=np.float32)
+        o32 = O.attention_output(A32, V, accumulate=np.float32)
+        stored = X.to_storage_values(o32, self.wl.dtype)
+        self.worst = {"step": t, "seq": s, "element": tuple(int(x) for x in i), "device_gap": float(gap[i]),
+                      "f32_oracle_gap": float(abs(o32[i] - ref[i])),
+                      "f32_oracle_rounded_to_storage_gap": float(abs(stored[i] - ref[i]))}
+
+    def report(self, label: str) -> str:
+        w = self.worst
+        if w is None:
+            return f"{label}: no probe taken"
+        return (f"{label}: worst probed output element at step {w['step']} seq {w['seq']} {w['element']}: "
+                f"device off by {w['device_gap']:.3e}; the float32-accumulating oracle is off by "
+                f"{w['f32_oracle_gap']:.3e}, and by {w['f32_oracle_rounded_to_storage_gap']:.3e} once its output "
+                f"is rounded to {self.wl.dtype} like the device's")
 
 
 def storage_to_values(a: np.ndarray, dtype: str) -> np.ndarray:
@@ -82,11 +148,23 @@ class Lockstep:
         self.max_out_err = 0.0
         self.max_score_rel = 0.0
         self.evictions = 0
+        self.probe = RoundingProbe(wl)
+        self.probe_every = 0               # > 0: take the rounding probe every that many steps
 
     def close(self):
         if self.ctx:
             self.mkv.mkv_destroy(self.ctx)
             self.ctx = None
+
+    def follow_from_gpu(self, s: int):
+        """Starts following an active sequence from the device's own state (a mid-run window)."""
+        assert s in self.active and s not in self.oracles
+        self.oracles[s] = oracle_from_gpu(self.mkv, self.ctx, self.wl, self.layer, s)
+        self.seqs.append(s)
+
+    def unfollow(self, s: int):
+        del self.oracles[s]
+        self.seqs.remove(s)
 
     def _device_kv(self, n):
         """N(0,1) rows drawn on the device in the storage dtype (for sequences nobody follows)."""
@@ -156,6 +234,8 @@ class Lockstep:
             self.max_out_err = max(self.max_out_err, float(err.max()))
             assert np.all(err <= atol + rtol * np.abs(ref)), \
                 f"step {t} seq {s}: attention output off by {err.max():.3e}"
+            if self.probe_every and t % self.probe_every == 0:
+                self.probe.look(st, q[s], got[s], ref, t, s)
             if check_abar:
                 ga, _ = self.mkv.mkv_read_probs(self.ctx, self.layer, s, wl.n_q_heads, wl.capacity)
                 assert ga.shape == abar.shape
@@ -253,3 +333,183 @@ class Lockstep:
             k, v = self.mkv.mkv_read_kv(self.ctx, self.layer, s, 1, g, wl.head_dim, dt)
             assert np.array_equal(storage_to_values(k, wl.dtype), k0[:, g])
             assert np.array_equal(storage_to_values(v, wl.dtype), v0[:, g])
+
+
+class FreeRun:
+    """The library's own capacity check -- an auto-evicting context, the path a caller runs --
+    under the oracle's eyes, with no score injection.
+
+    A second, never-evicting context (the "twin") takes the same steps on the same inputs, so that
+    after each step it holds the float32 scores the auto context had *before* its eviction.  The
+    oracle's selection (Eq. 8) run on those exact bits must name the tokens the auto context
+    dropped: retained positions, scores and rows bit for bit.  The oracle's own run (float64 state)
+    is compared every step at the score tolerance; where its selection differs from the one made
+    on the device's bits, the tokens in question must be a near-tie at the cut -- counted, never
+    skipped -- and the oracle then removes the device's set (Eq. 9) so that the two runs remain
+    comparable to the end.  The twin evicts through mkv_evict (selection kernel + row mover), the
+    auto context through whatever mkv_decode_step launches (at the paper's cadence: the arg-min
+    taken by the finishing kernel and the one-row shift)."""
+
+    def __init__(self, mkv, wl: X.Workload, seqs=None, active=None, per_head: bool = False,
+                 attn_variant: int = 0, split_keys: int = 0, device_fill_unfollowed: bool = False,
+                 layer: int = 0, auto_capacity: int | None = None):
+        self.mkv, self.wl, self.layer, self.per_head = mkv, wl, layer, per_head
+        self.seqs = list(range(wl.batch)) if seqs is None else list(seqs)
+        self.active = list(self.seqs) if active is None else list(active)
+        assert set(self.seqs) <= set(self.active)
+        self.device_fill = device_fill_unfollowed
+        mode = mkv.MKV_SCORE_PER_KV_HEAD if per_head else mkv.MKV_SCORE_LAYER_MEAN
+        kw = dict(layers=layer + 1, split_keys=split_keys, attn_variant=attn_variant, score_mode=mode)
+        self.auto = make_ctx(mkv, wl, manual_evict=False, decode_capacity=auto_capacity, **kw)
+        self.twin = make_ctx(mkv, wl, manual_evict=True, **kw)
+        self.n_vec = wl.n_kv_heads if per_head else 1
+        self.oracles = {s: oracle_state(wl, "per_kv_head" if per_head else "layer_mean") for s in self.seqs}
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        self.out_a = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda")
+        self.out_t = torch.zeros_like(self.out_a)
+        self.mask = np.zeros(wl.batch, dtype=np.uint8)
+        self.mask[self.active] = 1
+        self.dt = mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32
+        self.max_out_err = self.max_score_rel = 0.0
+        self.evictions = self.near_ties = 0
+        self.evicted_slots = []            # slot of every one-token eviction of a followed sequence
+
+    def close(self):
+        for c in (self.auto, self.twin):
+            if c:
+                self.mkv.mkv_destroy(c)
+        self.auto = self.twin = None
+
+    def prefill(self):
+        wl = self.wl
+        for s in self.active:
+            if self.device_fill and s not in self.oracles:
+                m = X.prefill_len(wl, s)
+                dt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+                dk = torch.randn((m, wl.n_kv_heads, wl.head_dim), device="cuda").to(dt)
+                dv = torch.randn((m, wl.n_kv_heads, wl.head_dim), device="cuda").to(dt)
+            else:
+                k, v = X.prefill_kv(wl, self.layer, s)
+                dk, dv = to_device(k, wl.dtype), to_device(v, wl.dtype)
+                if s in self.oracles:
+                    self.oracles[s].prefill_append(k, v)
+            if dk.shape[0]:
+                for c in (self.auto, self.twin):
+                    self.mkv.mkv_prefill_append(c, self.layer, s, dk.data_ptr(), dv.data_ptr(), dk.shape[0])
+            torch.cuda.synchronize()
+
+    def load_snapshot(self, n_d: int, t_now: int, scores=None):
+        """Both contexts (and the oracles) start from the same synthetic mid-run decode pool;
+        `scores`: float32[n_d] to use instead of the generator's (planted minima and ties)."""
+        assert not self.per_head
+        wl = self.wl
+        for s in self.active:
+            k, v, sc, pos = X.decode_snapshot(wl, self.layer, s, n_d, t_now)
+            if scores is not None:
+                sc = np.asarray(scores[s] if isinstance(scores, dict) else scores, dtype=np.float32)
+            dk, dv = to_device(k, wl.dtype), to_device(v, wl.dtype)
+            for c in (self.auto, self.twin):
+                self.mkv.mkv_load_decode(c, self.layer, s, dk.data_ptr(), dv.data_ptr(), sc, pos, t_now)
+            if s in self.oracles:
+                self.oracles[s].load_decode(k, v, sc, pos, t_now)
+
+    def follow_from_gpu(self, s: int):
+        """Starts following an active sequence from the device's own state (a mid-run window)."""
+        assert s in self.active and s not in self.oracles
+        self.oracles[s] = oracle_from_gpu(self.mkv, self.auto, self.wl, self.layer, s, self.per_head)
+        self.seqs.append(s)
+
+    def unfollow(self, s: int):
+        del self.oracles[s]
+        self.seqs.remove(s)
+
+    def _scores(self, ctx, s, v):
+        if self.per_head:
+            self.mkv.mkv_set_score_view(ctx, v)
+        return self.mkv.mkv_read_scores(ctx, self.layer, s)
+
+    def _rows(self, ctx, s):
+        return [self.mkv.mkv_read_kv(ctx, self.layer, s, 0, g, self.wl.head_dim, self.dt)
+                for g in range(self.wl.n_kv_heads)]
+
+    def step(self, t: int, check_rows: bool = False):
+        wl, mkv, L = self.wl, self.mkv, self.layer
+        q, k, v = X.step_batch(wl, L, t)
+        dq, dk, dv = (to_device(a, wl.dtype) for a in (q, k, v))
+        mkv.mkv_decode_step(self.auto, L, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), self.out_a.data_ptr(), self.mask)
+        mkv.mkv_decode_step(self.twin, L, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), self.out_t.data_ptr(), self.mask)
+        torch.cuda.synchronize()
+        # same kernels on bit-identical pools: any difference means the two contexts have split
+        assert torch.equal(self.out_a, self.out_t), f"step {t}: auto and twin contexts disagree on Att"
+        got = from_device(self.out_a)
+        rtol, atol = OUT_TOL[wl.dtype]
+        for s in self.active:
+            if s in self.oracles:
+                continue
+            if mkv.mkv_get_lens(self.twin, L, s)[1] > wl.evict_trigger:
+                mkv.mkv_evict(self.twin, L, s)
+        for s in self.seqs:
+            st = self.oracles[s]
+            ref, _ = st.decode_step(q[s], k[s], v[s], auto_evict=False)
+            err = np.abs(got[s] - ref)
+            self.max_out_err = max(self.max_out_err, float(err.max()))
+            assert np.all(err <= atol + rtol * np.abs(ref)), f"step {t} seq {s}: attention output off by {err.max():.3e}"
+            fire = st.n_decode > wl.evict_trigger
+            rows_before = self._rows(self.twin, s) if (fire and check_rows) else None
+            expect = []
+            for vec in range(self.n_vec):
+                S_g, P_g = self._scores(self.twin, s, vec)          # what the auto context selected on
+                assert np.array_equal(P_g, st.pos[vec].astype(np.int32)), f"step {t} seq {s} vec {vec}: positions differ"
+                ref_I = st.I[vec]
+                e = np.abs(S_g.astype(np.float64) - ref_I)
+                self.max_score_rel = max(self.max_score_rel, float(np.max(e / (np.abs(ref_I) + 1e-30))))
+                assert np.all(e <= SCORE_RTOL * np.abs(ref_I) + SCORE_ATOL), \
+                    f"step {t} seq {s} vec {vec}: score mismatch, worst rel {np.max(e / (np.abs(ref_I) + 1e-30)):.3e}"
+                if not fire:
+                    expect.append((S_g, P_g, None))
+                    continue
+                ov = O.overflow(S_g.size, wl.decode_budget)
+                E_g = O.select_evict(S_g, P_g, ov, wl.recent_window)               # Eq. 8 on the device's bits
+                E_o = O.select_evict(ref_I.astype(np.float32), st.pos[vec], ov, wl.recent_window)
+                if not np.array_equal(E_g, E_o):
+                    diff = np.setxor1d(E_g, E_o)
+                    cut = np.sort(S_g[:S_g.size - wl.recent_window])[ov - 1]
+                    slack = 2 * (SCORE_RTOL * abs(float(cut)) + SCORE_ATOL)
+                    assert np.all(np.abs(S_g[diff] - cut) <= slack) and \
+                        np.all(np.abs(ref_I[diff] - float(cut)) <= 2 * slack), \
+                        f"step {t} seq {s} vec {vec}: selections differ beyond a near-tie at the cut"
+                    self.near_ties += 1
+                st.remove(vec, E_g)
+                if ov == 1:
+                    self.evicted_slots.append(int(E_g[0]))
+                keep = O.survivors(S_g.size, E_g)
+                expect.append((S_g[keep], P_g[keep], keep))
+            if fire:
+                self.evictions += 1
+                mkv.mkv_evict(self.twin, L, s)
+            for vec in range(self.n_vec):
+                S_e, P_e, keep = expect[vec]
+                for name, ctx in (("auto", self.auto), ("twin", self.twin)):
+                    S_c, P_c = self._scores(ctx, s, vec)
+                    assert np.array_equal(P_c, P_e), f"step {t} seq {s} vec {vec}: {name} context retained another set"
+                    assert np.array_equal(S_c.view(np.uint32), S_e.view(np.uint32)), \
+                        f"step {t} seq {s} vec {vec}: {name} context's scores differ"
+            if self.per_head:
+                mkv.mkv_set_score_view(self.auto, 0)
+                mkv.mkv_set_score_view(self.twin, 0)
+            if check_rows:
+                rows_a = self._rows(self.auto, s)
+                rows_t = self._rows(self.twin, s)
+                for g in range(wl.n_kv_heads):
+                    vec = g if self.per_head else 0
+                    Kd = st.Kd[vec][:, 0 if self.per_head else g]
+                    Vd = st.Vd[vec][:, 0 if self.per_head else g]
+                    for name, rows in (("auto", rows_a), ("twin", rows_t)):
+                        assert np.array_equal(storage_to_values(rows[g][0], wl.dtype).astype(np.float64), Kd), \
+                            f"step {t} seq {s} head {g}: {name} K rows differ from the oracle's pool"
+                        assert np.array_equal(storage_to_values(rows[g][1], wl.dtype).astype(np.float64), Vd), \
+                            f"step {t} seq {s} head {g}: {name} V rows differ from the oracle's pool"
+                    if rows_before is not None:
+                        keep = expect[vec][2]
+                        assert np.array_equal(rows_a[g][0], rows_before[g][0][keep])
+                        assert np.array_equal(rows_a[g][1], rows_before[g][1][keep])
