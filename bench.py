@@ -11,6 +11,11 @@ Prints ONE JSON line.  `value` = microseconds per decode step per layer (lower i
 tokens/s and the whole-step algorithmic GB/s beside it; `roofline` covers the attention kernel,
 timed with start/stop HIP events attached to every launch in a second pass of the same steps; `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
+
+The metric is the step *with* its share of evictions, so the timed region always consists of whole
+eviction cycles: --steps is rounded up to a multiple of the workload's eviction chunk (64 for the
+Llama-shaped layers, 1 for the Qwen-shaped one) and the count actually timed is reported as
+`steps_timed`.  Any such window holds the same number of evictions wherever it starts.
 """
 from __future__ import annotations
 
@@ -50,7 +55,9 @@ def parse_args():
                     help="also time score-rule variants of the main workload (same kernels, other parameters)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB elementwise pass (for scaling rocprofv3's FETCH_SIZE/WRITE_SIZE)")
-    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--cpu-seconds", type=float, default=16.0, help="CPU time budget of the oracle baseline (two legs)")
+    ap.add_argument("--cpu-leg", default="", help="internal: 'seq,seconds,threads' -- run one worker leg of the CPU "
+                                                  "baseline on that sequence and print [steps, wall s, cpu s]")
     return ap.parse_args()
 
 
@@ -192,35 +199,66 @@ def time_region(job: Job, steps: int):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
-def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0):
+def whole_cycles(wl, steps, q_len=0):
+    """`steps` rounded up to whole eviction cycles of the workload (calls, when a call appends
+    q_len tokens): the pools return to the budget every `chunk` appended tokens."""
+    if wl.evict_trigger >= 2**31 - 1:
+        return steps
+    chunk = wl.evict_trigger - wl.decode_budget + 1
+    nq = max(1, q_len)
+    cycle = -(-chunk // nq)                     # calls per cycle (the last call of a cycle crosses the trigger)
+    return -(-max(1, steps) // cycle) * cycle
+
+
+def simulate(job, n_now, steps):
+    """Algorithmic bytes and evicting steps over `steps` calls from the pool sizes n_now
+    (deterministic: + q_len per call, back to the budget once above the trigger).  Returns
+    (whole-step bytes, attention bytes, evicting steps, pool sizes afterwards)."""
+    wl, nq = job.wl, max(1, job.q_len)
+    total_bytes = attn_bytes = evict_steps = 0
+    sim = list(n_now)
+    for _ in range(steps):
+        tb, ab = algorithmic_bytes(job, sim)
+        total_bytes += tb
+        attn_bytes += ab
+        sim = [n + nq for n in sim]
+        if any(n > wl.evict_trigger for n in sim):
+            evict_steps += 1
+        sim = [wl.decode_budget if n > wl.evict_trigger else n for n in sim]
+    return total_bytes, attn_bytes, evict_steps, sim
+
+
+def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=True):
+    """evicts=False: a setting that is meant never to reach its trigger (the full-cache variant);
+    its window is timed as given."""
     job = Job(wl, split_keys, variant, gpc, q_len)
     nq = max(1, q_len)
+    requested = steps
+    if evicts:
+        steps = whole_cycles(wl, steps, q_len)
     try:
         run_steps(job, warmup)
-        # sizes the pools will have over the timed steps (deterministic: +1 per step, back to the
-        # budget once above the trigger)
         n_now = pool_sizes(job)
-        total_bytes = attn_bytes = 0
-        evict_steps = 0
-        sim = list(n_now)
-        for _ in range(steps):
-            tb, ab = algorithmic_bytes(job, sim)
-            total_bytes += tb
-            attn_bytes += ab
-            sim = [n + nq for n in sim]
-            if any(n > wl.evict_trigger for n in sim):
-                evict_steps += 1
-            sim = [wl.decode_budget if n > wl.evict_trigger else n for n in sim]
+        total_bytes, _, evict_steps, n_after = simulate(job, n_now, steps)
         gpu_s, wall_s = time_region(job, steps)
-        # second pass of the same number of steps with per-kernel events
+        assert pool_sizes(job) == n_after, "the pools did not move as the byte count assumes"
+        # second pass of the same number of steps with per-kernel events; its attention bytes are
+        # counted for the pool sizes of that pass
+        _, attn_bytes, evict_steps2, _ = simulate(job, n_after, steps)
         job.mkv.mkv_set_profiling(job.ctx, True)
         run_steps(job, steps)
         prof, psteps, pevict = job.mkv.mkv_read_profile(job.ctx)
         job.mkv.mkv_set_profiling(job.ctx, False)
         n_launch = steps * wl.n_layers
         assert psteps == n_launch
+        finite = evicts and wl.evict_trigger < 2**31 - 1
+        assert not finite or (evict_steps > 0 and pevict == evict_steps2 * wl.n_layers > 0), \
+            "a timed window of a workload that evicts must contain evictions"
         res = {
             "workload": wl.name,
+            "steps_requested": requested,
+            "steps_timed": steps,
+            "evicting_steps_in_timed_window": evict_steps,
             "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
             "ms_per_step": gpu_s * 1e3 / steps,
             "wall_ms_per_step": wall_s * 1e3 / steps,
@@ -288,28 +326,67 @@ def measure_producer(wl, hidden, steps, warmup):
         job.close()
 
 
-def cpu_baseline(wl, seconds):
-    """The oracle as it stands, one sequence of the workload from a budget-full pool, timed for
-    about `seconds`; scaled to the whole batch (sequences are independent)."""
+def _oracle_leg(job):
+    """One timed leg of the CPU baseline (also the body of a worker process): the oracle as it
+    stands on one sequence of the workload, from a budget-full decode pool, for about `seconds`,
+    with the BLAS/OpenMP pools of numpy limited to `threads`.  Returns (steps, wall s, cpu s)."""
+    wl, seq, seconds, threads = job
+    from threadpoolctl import threadpool_limits
     from oracle import momentkv_oracle as O
     from paper_2605_29873_amd import inputs as X
-    st = O.MomentKVState(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.decode_budget, wl.alpha,
-                         wl.evict_trigger, wl.recent_window)
-    st.prefill_append(*X.prefill_kv(wl, 0, 0))
-    t_now = 4 * wl.capacity
-    st.load_decode(*X.decode_snapshot(wl, 0, 0, wl.decode_budget, t_now), t_now)
-    inputs = [X.step_inputs(wl, 0, 0, t_now + t) for t in range(8)]
-    n = 0
-    c0, t0 = time.process_time(), time.perf_counter()
-    while time.perf_counter() - t0 < seconds and n < 4096:
-        st.decode_step(*inputs[n % len(inputs)])
-        n += 1
-    wall, cpu = time.perf_counter() - t0, time.process_time() - c0
-    per_seq_step_us = wall / n * 1e6
-    return {"value": per_seq_step_us * wl.batch, "unit": "us per decode step per layer",
-            "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
-            "sample": f"sequence 0 (prefill {X.prefill_len(wl, 0)}) of layer 0, {n} steps from a budget-full decode pool, "
-                      f"{per_seq_step_us:.0f} us per sequence-step x batch {wl.batch}; numpy fp64"}
+    with threadpool_limits(limits=threads):
+        st = O.MomentKVState(wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.decode_budget, wl.alpha,
+                             wl.evict_trigger, wl.recent_window)
+        st.prefill_append(*X.prefill_kv(wl, 0, seq))
+        t_now = 4 * wl.capacity
+        st.load_decode(*X.decode_snapshot(wl, 0, seq, wl.decode_budget, t_now), t_now)
+        inputs = [X.step_inputs(wl, 0, seq, t_now + t) for t in range(8)]
+        n = 0
+        c0, t0 = time.process_time(), time.perf_counter()
+        while time.perf_counter() - t0 < seconds and n < 4096:
+            st.decode_step(*inputs[n % len(inputs)])
+            n += 1
+        return n, time.perf_counter() - t0, time.process_time() - c0
+
+
+def cpu_baseline(wl, seconds):
+    """The oracle as it stands, timed on this machine's host cores in two forms, each for about
+    half of `seconds`: (a) one thread, sequence 0; (b) all cores this process may use -- the
+    sequences of the batch are independent, so min(batch, cores) worker processes take one sequence
+    each and share the cores' threads between them.  Both are scaled to one decode step of the whole
+    batch of one layer.  Runs before anything touches the GPU (the workers are fresh processes)."""
+    import subprocess
+    from paper_2605_29873_amd import inputs as X
+    share = len(os.sched_getaffinity(0))
+    for var in ("OMP_NUM_THREADS",):               # a machine's stated CPU share, where it sets one
+        if os.environ.get(var, "").isdigit():
+            share = max(1, min(share, int(os.environ[var])))
+    n1, wall1, _ = _oracle_leg((wl, 0, seconds / 2, 1))
+    single_us = wall1 / n1 * 1e6 * wl.batch
+    workers = max(1, min(wl.batch, share))
+    threads = max(1, share // workers)
+    # one child process per worker, each this script again with --cpu-leg (prints its three numbers)
+    key = next(k for k, w in X.workloads().items() if w == wl)
+    procs = [subprocess.Popen([sys.executable, os.path.abspath(__file__), "--workload", key,
+                               "--cpu-leg", f"{s},{seconds / 2},{threads}"], stdout=subprocess.PIPE, text=True)
+             for s in range(workers)]
+    legs = []
+    for p in procs:
+        out, _ = p.communicate()
+        if p.returncode != 0:
+            raise RuntimeError("a CPU-baseline worker failed")
+        n, wall, cpu_s = json.loads(out.strip().splitlines()[-1])
+        legs.append((n, wall, cpu_s))
+    rate = sum(n / wall for n, wall, _ in legs)                   # sequence-steps per second, all workers
+    used = sum(cpu / wall for _, wall, cpu in legs)
+    return {"value": wl.batch / rate * 1e6, "unit": "us per decode step per layer",
+            "cores": max(1, int(round(used))), "kind": "oracle",
+            "sample": f"layer 0 from budget-full decode pools, numpy fp64; all cores: {workers} worker processes x "
+                      f"{threads} threads on sequences 0..{workers - 1} for {seconds / 2:.0f} s "
+                      f"({sum(n for n, _, _ in legs)} sequence-steps), scaled to batch {wl.batch}; single thread: "
+                      f"sequence 0 (prefill {X.prefill_len(wl, 0)}), {n1} steps",
+            "single_thread": {"value": single_us, "unit": "us per decode step per layer", "cores": 1},
+            "nproc": os.cpu_count(), "cpu_share": share}
 
 
 def variant_workloads(wl):
@@ -353,15 +430,20 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+    from paper_2605_29873_amd import inputs as X
+    wls = X.workloads()
+    wl = wls[args.workload]
+    if args.cpu_leg:
+        seq, seconds, threads = args.cpu_leg.split(",")
+        print(json.dumps(_oracle_leg((wl, int(seq), float(seconds), int(threads)))))
+        return
+    cpu = None if args.no_cpu_baseline else cpu_baseline(wl, args.cpu_seconds)   # before the GPU is touched
     import torch
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     import paper_2605_29873_amd.binding as mkv
-    from paper_2605_29873_amd import inputs as X
     mkv.load()
-    wls = X.workloads()
-    wl = wls[args.workload]
     if args.calibrate_copy:   # a plain elementwise pass of known size: 1 GiB read + 1 GiB written
         src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
@@ -373,9 +455,8 @@ def main():
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w = wls[name]
-        # many-layer jobs: one whole eviction cycle (the pools evict every `chunk` steps)
-        chunk = w.evict_trigger - w.decode_budget + 1
-        steps = args.steps if w.n_layers == 1 else max(chunk, 16)
+        # many-layer jobs: one whole eviction cycle (measure() rounds up to whole cycles)
+        steps = args.steps if w.n_layers == 1 else 1
         warm = args.warmup if w.n_layers == 1 else 8
         try:
             others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant, args.groups_per_cu)
@@ -386,6 +467,7 @@ def main():
         "value": main_res["us_per_step_per_layer"],
         "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "steps_timed": main_res["steps_timed"],      # --steps rounded up to whole eviction cycles
         "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16",   # bf16 operands, fp32 accumulation and scores
@@ -418,12 +500,13 @@ def main():
     if args.variants:
         line["variants"] = {}
         for name, w in variant_workloads(wl).items():
-            r = measure(w, min(args.steps, 128), 8, args.split_keys, args.attn_variant, args.groups_per_cu)
-            line["variants"][name] = {k: r[k] for k in ("us_per_step_per_layer", "tokens_per_s", "attn_kernel_us",
+            r = measure(w, min(args.steps, 128), 8, args.split_keys, args.attn_variant, args.groups_per_cu,
+                        evicts=not name.startswith("full cache"))
+            line["variants"][name] = {k: r[k] for k in ("us_per_step_per_layer", "steps_timed", "tokens_per_s", "attn_kernel_us",
                                                          "finish_kernel_us", "evict_us_per_evicting_launch",
                                                          "evicting_launches", "pool_tokens_per_layer")}
-    if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(wl, args.cpu_seconds)
+    if cpu is not None:
+        line["cpu_baseline"] = cpu
     print(json.dumps(line))
 
 

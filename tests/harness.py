@@ -17,6 +17,24 @@ OUT_TOL = {"bf16": (2e-2, 2e-3), "f32": (1e-4, 1e-5)}
 SCORE_RTOL, SCORE_ATOL = 1e-4, 1e-9
 
 
+class Progress:
+    """A line on the real stdout every `every` seconds from inside a long test (pytest's capture is
+    suspended for it), so that a run that follows a workload for minutes is seen to be alive."""
+
+    def __init__(self, capsys, label: str, every: float = 20.0):
+        import time
+        self.capsys, self.label, self.every = capsys, label, every
+        self.clock = time.monotonic
+        self.t0 = self.last = self.clock()
+
+    def tick(self, what: str):
+        now = self.clock()
+        if now - self.last >= self.every:
+            self.last = now
+            with self.capsys.disabled():
+                print(f"  [{self.label}] {what}, {now - self.t0:.0f} s", flush=True)
+
+
 def to_device(x: np.ndarray, dtype: str) -> torch.Tensor:
     """Storage-exact float32 values -> device tensor in the storage dtype."""
     if dtype == "bf16":

@@ -11,7 +11,7 @@ import torch
 
 from oracle import momentkv_oracle as O
 from paper_2605_29873_amd import inputs as X
-from tests.harness import FreeRun, to_device
+from tests.harness import FreeRun, Progress, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -148,7 +148,7 @@ def test_chunked_auto_eviction_free_run_under_the_oracle(mkv, name, changes, ste
 
 
 @pytest.mark.slow
-def test_cfg4_qwen_layer_from_an_empty_pool_2048_steps(mkv):
+def test_cfg4_qwen_layer_from_an_empty_pool_2048_steps(mkv, capsys):
     """The Qwen-shaped layer at full size (8 sequences x 8192 prompt tokens, 28/4 heads, budget 512,
     window 32, alpha 0.8), all sequences active, from an empty decode pool through 2048 steps:
     1536 one-token evictions per sequence through the finishing kernel's arg-min and the one-row
@@ -159,6 +159,7 @@ def test_cfg4_qwen_layer_from_an_empty_pool_2048_steps(mkv):
     fr = FreeRun(mkv, wl, seqs=[5], active=range(wl.batch), device_fill_unfollowed=True)
     windows = {560: 1, 900: 6, 1400: 3, 1900: 0}        # first step of the window -> sequence
     closing = {}
+    alive = Progress(capsys, "cfg4 free run")
     try:
         fr.prefill()
         for t in range(2048):
@@ -168,6 +169,7 @@ def test_cfg4_qwen_layer_from_an_empty_pool_2048_steps(mkv):
             if t in closing:
                 fr.unfollow(closing[t])
             fr.step(t, check_rows=(t % 256 == 0 or t in closing or t == 2047))
+            alive.tick(f"step {t} of 2048, {fr.evictions} evictions")
         assert fr.evictions == (2048 - 512) + 4 * 48
     finally:
         fr.close()

@@ -9,7 +9,7 @@ import torch
 
 from oracle import momentkv_oracle as O
 from paper_2605_29873_amd import inputs as X
-from tests.harness import Lockstep, make_ctx, to_device, from_device, oracle_state, oracle_from_gpu, OUT_TOL
+from tests.harness import Lockstep, Progress, make_ctx, to_device, from_device, oracle_state, oracle_from_gpu, OUT_TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -87,7 +87,7 @@ def test_cfg3_ragged_batch_full_size_sampled(mkv):
 
 
 @pytest.mark.slow
-def test_cfg3_whole_sequence_lockstep_with_windows_from_device_state(mkv):
+def test_cfg3_whole_sequence_lockstep_with_windows_from_device_state(mkv, capsys):
     """The ragged 16-sequence Llama-shaped layer at full size, every sequence active, for the whole
     8192-step run from empty decode pools: sequence 10 is followed by the oracle at every step (96
     evictions of 64 tokens, all sixteen bursts, alpha = 0.95 saturation); the other fifteen hold
@@ -101,6 +101,7 @@ def test_cfg3_whole_sequence_lockstep_with_windows_from_device_state(mkv):
     windows = {2300: 3, 3900: 12, 5600: 7, 7300: 15}     # first step of the window -> sequence
     closing = {}
     ls.prefill()
+    alive = Progress(capsys, "cfg3 whole run")
     try:
         for t in range(wl.steps):
             if t in windows:
@@ -109,6 +110,7 @@ def test_cfg3_whole_sequence_lockstep_with_windows_from_device_state(mkv):
             if t in closing:
                 ls.unfollow(closing[t])
             ls.step(t, check_abar=(t % 64 == 0))
+            alive.tick(f"step {t} of {wl.steps}, {ls.evictions} evictions")
         ls.check_prefill_untouched(10)
     finally:
         ls.close()
@@ -154,7 +156,7 @@ def test_cfg5_full_size_one_layer_of_32_sampled(mkv):
 
 
 @pytest.mark.slow
-def test_cfg5_windows_from_a_device_run_of_the_full_context(mkv):
+def test_cfg5_windows_from_a_device_run_of_the_full_context(mkv, capsys):
     """The full 86 GB context (32 layers x 32 sequences, 16384 prompt tokens each) as a running job:
     every layer starts from a device-drawn pool 70 tokens below its trigger and all 32 layers step
     together, so that whole-context eviction cycles take place on scores the device accumulated
@@ -172,8 +174,10 @@ def test_cfg5_windows_from_a_device_run_of_the_full_context(mkv):
     t_now = 4 * wl.capacity
     n0 = wl.evict_trigger - 70
     rng = np.random.default_rng(5)
+    alive = Progress(capsys, "cfg5 windows")
     try:
         for layer in range(wl.n_layers):
+            alive.tick(f"filling layer {layer}")
             for s in range(wl.batch):
                 k, v = draw(wl.prefill_max, wl.n_kv_heads, wl.head_dim), draw(wl.prefill_max, wl.n_kv_heads, wl.head_dim)
                 mkv.mkv_prefill_append(ctx, layer, s, k.data_ptr(), v.data_ptr(), wl.prefill_max)
@@ -205,6 +209,7 @@ def test_cfg5_windows_from_a_device_run_of_the_full_context(mkv):
                     mkv.mkv_evict(ctx, layer, -1)
             if n_d > wl.evict_trigger:
                 n_d = wl.decode_budget
+            alive.tick(f"step {t}, {ls.evictions} followed evictions")
             if follow and t + 1 == follow[2]:
                 ls.unfollow(follow[1])
                 follow = None
