@@ -160,6 +160,27 @@ int mkv_project_append(mkv_ctx* ctx, int layer, const void* x, const void* w_k, 
 int mkv_decode_step(mkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
                     void* out, const uint8_t* seq_mask);
 
+/* mkv_decode_step for callers that cannot allocate device memory and want none set aside per
+ * context: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, same results, same kernels; the step's scratch (per-work-group partial results,
+ * decode logits, head means, the compaction map and selection keys) lives in a static array of
+ * MKV_STATIC_SCRATCH_BYTES inside the library's code object instead of the context's arena.  Every
+ * GPU the library runs on holds one copy of that array until the process ends; its address is
+ * looked up once per GPU (in mkv_create, else in the first call).  The call allocates nothing, on
+ * the host or the device.
+ *   - MKV_ERR_CAPACITY, with nothing launched, when the step's scratch would not fit; the message
+ *     gives both sizes.  The need grows with batch * n_q_heads * decode_capacity (logits) and with
+ *     the number of attention work-groups; the five reference workloads need 2 .. 23 MiB.
+ *   - All contexts on one GPU share the array and it keeps the last call's contents.  Nothing in
+ *     it has to be cleared between calls: every word a kernel of the step reads was written
+ *     earlier in the same call.  Two calls that overlap in time on one GPU (different streams)
+ *     race on it: keep them on one stream or order them.
+ *   - mkv_read_probs after this call reads the array, so it is only valid until the next
+ *     mkv_decode_step_static on that GPU. */
+#define MKV_STATIC_SCRATCH_BYTES (32u << 20)
+int mkv_decode_step_static(mkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
+                           void* out, const uint8_t* seq_mask);
+
 /* q_len decode steps of every active sequence in one pass over the cache (chunked or speculative
  * decoding): the result equals q_len consecutive mkv_decode_step calls whose capacity check is
  * held back until the last of them.

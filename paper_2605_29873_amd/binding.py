@@ -21,7 +21,7 @@ MKV_ERR_CAPACITY, MKV_ERR_NOMEM, MKV_ERR_HIP = -4, -5, -6
 MKV_NEVER_EVICT = 2**31 - 1
 
 EXPORTS = ["mkv_required_bytes", "mkv_create", "mkv_destroy", "mkv_prefill_append", "mkv_prefill_compress", "mkv_project_append",
-           "mkv_decode_step", "mkv_decode_step_multi", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
+           "mkv_decode_step", "mkv_decode_step_static", "mkv_decode_step_multi", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
            "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_set_score_view", "mkv_get_lens", "mkv_set_profiling",
            "mkv_read_profile", "mkv_last_error"]
 
@@ -65,6 +65,7 @@ def load() -> C.CDLL:
     lib.mkv_prefill_compress.argtypes = [vp, i32, i32, vp, i32]
     lib.mkv_project_append.argtypes = [vp, i32, vp, vp, vp, i32, vp, C.c_float, vp]
     lib.mkv_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp]
+    lib.mkv_decode_step_static.argtypes = [vp, i32, vp, vp, vp, vp, vp]
     lib.mkv_decode_step_multi.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
     lib.mkv_evict.argtypes = [vp, i32, i32]
     lib.mkv_read_scores.argtypes = [vp, i32, i32, vp, vp, i32, C.POINTER(i32)]
@@ -136,6 +137,14 @@ def mkv_decode_step(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, seq_mask=None) -> 
         seq_mask = np.ascontiguousarray(seq_mask, dtype=np.uint8)
         mp = seq_mask.ctypes.data
     _check(ctx, load().mkv_decode_step(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, mp))
+
+
+def mkv_decode_step_static(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, seq_mask=None) -> None:
+    mp = None
+    if seq_mask is not None:
+        seq_mask = np.ascontiguousarray(seq_mask, dtype=np.uint8)
+        mp = seq_mask.ctypes.data
+    _check(ctx, load().mkv_decode_step_static(ctx, layer, q_ptr, k_ptr, v_ptr, out_ptr, mp))
 
 
 def mkv_decode_step_multi(ctx, layer, q_len, q_ptr, k_ptr, v_ptr, out_ptr, seq_mask=None) -> None:

@@ -10,13 +10,42 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
 
 using namespace mkv;
 
+// Per-step scratch of mkv_decode_step_static: one array per GPU, part of the loaded code object, so
+// that the entry point never allocates.  Host code may only use the address hipGetSymbolAddress
+// returns for the current device (static_scratch_base below), never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)MKV_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once
+
+// Device address of the static scratch array on the current GPU.
+hipError_t static_scratch_base(char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char*)g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 constexpr size_t kAlign = 256;
 constexpr int kMaxGroups = 4096;          // attention work-groups per launch, at most
@@ -203,6 +232,7 @@ struct mkv_ctx {
   int last_layer;
   int view;            // score vector the read/write helpers address (mkv_set_score_view)
   int last_q_len;      // query rows of the step taken last
+  Scratch last_sc;     // scratch the last decode step ran on (mkv_read_probs reads it back)
   int target_groups;   // attention work-groups a launch aims for: compute units x groups per unit
   int mq_target_groups;  // same for the multi-query kernel
   std::string err;
@@ -247,6 +277,36 @@ Scratch scratch_view(const mkv_ctx* c) {
   return s;
 }
 
+// The scratch of one decode step laid out in the static array instead of the arena: the same
+// regions as in make_layout, sized for this launch (`slots` partial slots of `rows` rows, `q_len`
+// query rows per sequence).  Returns the bytes needed; fills *out when they fit.
+size_t carve_static(const mkv_ctx* c, char* base, size_t slots, int rows, int q_len, Scratch* out) {
+  const size_t B = c->cfg.batch, H = c->cfg.n_q_heads, D = c->cfg.head_dim, S = c->lay.S, cap = c->lay.cap;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  const size_t part_o = take(slots * rows * D * 4);
+  const size_t part_ml = take(slots * rows * 2 * 4);
+  const size_t offs = take((B + 1) * 8);
+  const size_t logits = take(B * H * q_len * ((cap + 63) / 64 * 64) * 4);
+  const size_t abar = take(B * S * cap * 4);
+  const size_t lse = take(B * H * q_len * 4);
+  const size_t src_map = take(B * S * cap * 4);
+  const size_t evict_info = take(B * S * 2 * 4);
+  const size_t evict_key = take(B * S * 8);
+  if (o <= kStaticScratchBytes) {
+    out->part_o = (float*)(base + part_o);
+    out->part_ml = (float*)(base + part_ml);
+    out->offs = (long long*)(base + offs);
+    out->logits = (float*)(base + logits);
+    out->abar = (float*)(base + abar);
+    out->lse = (float*)(base + lse);
+    out->src_map = (int32_t*)(base + src_map);
+    out->evict_info = (int32_t*)(base + evict_info);
+    out->evict_key = (unsigned long long*)(base + evict_key);
+  }
+  return o;
+}
+
 constexpr int kEvPerSlot = 6;
 
 // Folds the recorded slots into the sums (waits for the stream to drain first).
@@ -286,7 +346,7 @@ int set_device_int(mkv_ctx* c, int32_t* p, int32_t v) {
 // `selected`: the finishing kernel of the step just taken may have left the one-token selection
 // (single-query step with trigger == budget); it is used when every sequence that fires holds
 // exactly budget + 1 tokens.
-int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* fired = nullptr,
+int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, const Scratch& sc, bool* fired = nullptr,
               const KernelTimer* tm = nullptr, bool selected = false) {
   const int B = c->cfg.batch;
   bool any = false;
@@ -299,8 +359,8 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* f
   }
   if (fired) *fired = any;
   if (!any) return MKV_OK;
-  hipError_t e = selected ? launch_evict_one(c->shape, layer_view(c, layer), scratch_view(c), mask, c->stream, tm)
-                          : launch_evict(c->shape, layer_view(c, layer), scratch_view(c), mask, threshold, c->stream, tm);
+  hipError_t e = selected ? launch_evict_one(c->shape, layer_view(c, layer), sc, mask, c->stream, tm)
+                          : launch_evict(c->shape, layer_view(c, layer), sc, mask, threshold, c->stream, tm);
   if (e != hipSuccess) return fail_hip(c, e, "evict launch");
   for (int b = 0; b < B; ++b) {
     int32_t& n = c->h_nd[(size_t)layer * B + b];
@@ -312,8 +372,9 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, bool* f
 // One pass of Algorithm 1 over the active sequences of a layer, appending q_len tokens per
 // sequence; `mq` selects the multi-query kernels (q, k_new, v_new and out then carry q_len rows per
 // sequence).
+// `static_scratch`: the step's scratch is the per-GPU static array instead of the arena's regions.
 int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k_new, const void* v_new,
-         void* out, const uint8_t* seq_mask) {
+         void* out, const uint8_t* seq_mask, bool static_scratch = false) {
   if (!c) return MKV_ERR_ARG;
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!q || !out) return fail(c, MKV_ERR_ARG, "q and out must not be NULL");
@@ -367,7 +428,6 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     lens.offs[B] = run;
   }
   LayerView lv = layer_view(c, layer);
-  Scratch sc = scratch_view(c);
   hipEvent_t* pe = nullptr;
   KernelTimer t_attn, t_fin, t_ev;
   if (c->prof.on) {
@@ -392,6 +452,19 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
   const int n_groups = (int)((total_keys + R - 1) / R);
   hipError_t e;
+  Scratch sc = scratch_view(c);
+  if (static_scratch) {
+    char* base = nullptr;
+    e = static_scratch_base(&base);
+    if (e != hipSuccess) return fail_hip(c, e, "address of the static scratch array");
+    // partial slots this launch can touch: one per work-group plus one per (sequence, KV head, pass)
+    const size_t slots = (size_t)n_groups + (size_t)B * c->cfg.n_kv_heads * passes;
+    const int rows = mq ? 16 * mq_row_blocks(G, q_len) : c->lay.HL;
+    const size_t need = carve_static(c, base, slots, rows, q_len, &sc);
+    if (need > kStaticScratchBytes)
+      return fail(c, MKV_ERR_CAPACITY, fmt("this step needs %zu bytes of scratch, the static array holds %zu: use "
+                                           "mkv_decode_step", need, kStaticScratchBytes));
+  }
   if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return fail_hip(c, e, "attention launch");
@@ -409,11 +482,12 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   }
   c->last_layer = layer;
   c->last_q_len = q_len;
+  c->last_sc = sc;
   int rc = MKV_OK;
   if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
     bool fired = false;
     const bool selected = q_len == 1 && c->cfg.evict_trigger == c->cfg.decode_budget;
-    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, &fired, pe ? &t_ev : nullptr, selected);
+    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, sc, &fired, pe ? &t_ev : nullptr, selected);
     if (pe && fired) c->prof.evicted[c->prof.used] = 1;
   }
   if (pe) c->prof.used += 1;
@@ -475,7 +549,12 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   const size_t LB = (size_t)cfg->n_layers * cfg->batch;
   c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0); c->in_pool.assign(LB, 0);
   c->h_last_n.assign(cfg->batch, 0);
+  c->last_sc = scratch_view(c);
   hipError_t e = configure_kernels();
+  if (e == hipSuccess) {   // address of the static scratch array on this GPU, for mkv_decode_step_static
+    char* base = nullptr;
+    e = static_scratch_base(&base);
+  }
   {
     int dev = 0, cus = 256;
     if (e == hipSuccess) e = hipGetDevice(&dev);
@@ -626,6 +705,11 @@ int mkv_decode_step(mkv_ctx* c, int layer, const void* q, const void* k_new, con
   return step(c, layer, 1, c && c->lay.mfma_single, q, k_new, v_new, out, seq_mask);
 }
 
+int mkv_decode_step_static(mkv_ctx* c, int layer, const void* q, const void* k_new, const void* v_new,
+                           void* out, const uint8_t* seq_mask) {
+  return step(c, layer, 1, c && c->lay.mfma_single, q, k_new, v_new, out, seq_mask, true);
+}
+
 int mkv_decode_step_multi(mkv_ctx* c, int layer, int q_len, const void* q, const void* k_new,
                           const void* v_new, void* out, const uint8_t* seq_mask) {
   if (!c) return MKV_ERR_ARG;
@@ -647,7 +731,7 @@ int mkv_evict(mkv_ctx* c, int layer, int seq) {
       return fail(c, MKV_ERR_STATE, fmt("sequence %d: a projected row is waiting for its decode step", b));
     mask.w[b >> 6] |= 1ull << (b & 63);
   }
-  return run_evict(c, layer, mask, c->cfg.decode_budget);
+  return run_evict(c, layer, mask, c->cfg.decode_budget, scratch_view(c));
 }
 
 int mkv_read_scores(mkv_ctx* c, int layer, int seq, float* scores, int32_t* positions, int capacity,
@@ -748,7 +832,7 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
   const int n = c->h_last_n[seq];
   if (n_out) *n_out = n;
   if (abar && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
-  Scratch sc = scratch_view(c);
+  const Scratch& sc = c->last_sc;
   hipError_t e = hipSuccess;
   if (abar && n) e = hipMemcpyAsync(abar, sc.abar + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
   if (e == hipSuccess && lse_per_head) {
