@@ -192,6 +192,10 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
 
 constexpr int kMoveThreads = 1024;
 constexpr int kSliceBytes = 128;
+// 16 bytes in flight between a round's reads and its writes.  A native vector, not HIP's uint4
+// class: arrays of the class stayed in scratch memory (144 bytes per lane by the compiler's
+// resource remark), i.e. every moved row took a detour through memory.
+typedef __attribute__((ext_vector_type(4))) unsigned int row16_t;
 
 // Stable in-place row compaction.  grid (row slices, Hkv * 2, B): a work-group owns a 128-byte
 // column strip of one head's K or V pool and walks the destination slots upwards.  Because a
@@ -219,18 +223,18 @@ __global__ __launch_bounds__(kMoveThreads) void evict_move_kernel(const EvictArg
   const int off = (threadIdx.x % kLanesPerRow) * 16;
   const int r = threadIdx.x / kLanesPerRow;
   for (int d0 = first; d0 < n_new; d0 += kRows * kMoveUnroll) {
-    uint4 v[kMoveUnroll];
+    row16_t v[kMoveUnroll];
 #pragma unroll
     for (int u = 0; u < kMoveUnroll; ++u) {
       const int d = d0 + u * kRows + r;
-      if (d < n_new) v[u] = *reinterpret_cast<const uint4*>(pool + (size_t)map[d] * rowb + off);
+      v[u] = d < n_new ? *reinterpret_cast<const row16_t*>(pool + (size_t)map[d] * rowb + off) : row16_t{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_s_waitcnt(0);  // every source of this round has arrived
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < kMoveUnroll; ++u) {
       const int d = d0 + u * kRows + r;
-      if (d < n_new) *reinterpret_cast<uint4*>(pool + (size_t)d * rowb + off) = v[u];
+      if (d < n_new) *reinterpret_cast<row16_t*>(pool + (size_t)d * rowb + off) = v[u];
     }
   }
 }
@@ -263,7 +267,8 @@ __global__ __launch_bounds__(kMoveThreads) void evict_one_kernel(const EvictArgs
 #pragma unroll
     for (int u = 0; u < kItems; ++u) {
       const int d = e + u * kMoveThreads + (int)threadIdx.x;
-      if (d < n_new) { sv[u] = score[d + 1]; pv[u] = pos[d + 1]; }
+      sv[u] = d < n_new ? score[d + 1] : 0.f;
+      pv[u] = d < n_new ? pos[d + 1] : 0;
     }
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
@@ -287,18 +292,18 @@ __global__ __launch_bounds__(kMoveThreads) void evict_one_kernel(const EvictArgs
   const int off = (threadIdx.x % kLanesPerRow) * 16;
   const int r = threadIdx.x / kLanesPerRow;
   for (int d0 = e; d0 < n_new; d0 += kRows * U) {
-    uint4 v[U];
+    row16_t v[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int d = d0 + u * kRows + r;
-      if (d < n_new) v[u] = *reinterpret_cast<const uint4*>(pool + (size_t)(d + 1) * rowb + off);
+      v[u] = d < n_new ? *reinterpret_cast<const row16_t*>(pool + (size_t)(d + 1) * rowb + off) : row16_t{0u, 0u, 0u, 0u};
     }
     __builtin_amdgcn_s_waitcnt(0);  // every source of this round has arrived
     __syncthreads();
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int d = d0 + u * kRows + r;
-      if (d < n_new) *reinterpret_cast<uint4*>(pool + (size_t)d * rowb + off) = v[u];
+      if (d < n_new) *reinterpret_cast<row16_t*>(pool + (size_t)d * rowb + off) = v[u];
     }
   }
 }
