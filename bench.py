@@ -85,7 +85,9 @@ class Job:
             n_layers=wl.n_layers, batch=wl.batch, n_q_heads=wl.n_q_heads, n_kv_heads=wl.n_kv_heads,
             head_dim=wl.head_dim, dtype=mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32,
             max_prefill=wl.prefill_max, decode_budget=wl.decode_budget, evict_trigger=wl.evict_trigger,
-            decode_capacity=wl.capacity + max(0, q_len - 1), recent_window=wl.recent_window, alpha=wl.alpha,
+            # single-query steps: the library's default capacity (one append past the trigger, plus
+            # the spare slots of deferred compaction where that applies)
+            decode_capacity=(wl.capacity + q_len - 1) if q_len else 0, recent_window=wl.recent_window, alpha=wl.alpha,
             softmax_scale=0.0, score_mode=0, split_keys=split_keys, attn_variant=variant, groups_per_cu=gpc,
             max_q_len=q_len,
             stream=torch.cuda.current_stream().cuda_stream)
@@ -199,14 +201,27 @@ def time_region(job: Job, steps: int):
     return e0.elapsed_time(e1) * 1e-3, wall
 
 
-def whole_cycles(wl, steps, q_len=0):
+def deferred_compaction(wl, q_len=0, variant=0):
+    """Whether the library defers compaction for this workload at its default capacity (the rule
+    of include/mkv.h: trigger == budget, bf16 x 128, single-query steps, default kernel variant),
+    and the spare slots it then adds."""
+    on = (wl.evict_trigger == wl.decode_budget and wl.dtype == "bf16" and wl.head_dim == 128 and q_len == 0
+          and variant == 0)
+    return on, min(64, max(8, wl.decode_budget // 8))
+
+
+def whole_cycles(wl, steps, q_len=0, variant=0):
     """`steps` rounded up to whole eviction cycles of the workload (calls, when a call appends
-    q_len tokens): the pools return to the budget every `chunk` appended tokens."""
+    q_len tokens): the pools return to the budget every `chunk` appended tokens.  With deferred
+    compaction the cycle is the compaction's: spare slots + 1 steps."""
     if wl.evict_trigger >= 2**31 - 1:
         return steps
     chunk = wl.evict_trigger - wl.decode_budget + 1
     nq = max(1, q_len)
     cycle = -(-chunk // nq)                     # calls per cycle (the last call of a cycle crosses the trigger)
+    deferred, spare = deferred_compaction(wl, q_len, variant)
+    if deferred:
+        cycle = spare + 1
     return -(-max(1, steps) // cycle) * cycle
 
 
@@ -235,7 +250,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
     nq = max(1, q_len)
     requested = steps
     if evicts:
-        steps = whole_cycles(wl, steps, q_len)
+        steps = whole_cycles(wl, steps, q_len, variant)
     try:
         run_steps(job, warmup)
         n_now = pool_sizes(job)
@@ -252,13 +267,17 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
         n_launch = steps * wl.n_layers
         assert psteps == n_launch
         finite = evicts and wl.evict_trigger < 2**31 - 1
-        assert not finite or (evict_steps > 0 and pevict == evict_steps2 * wl.n_layers > 0), \
-            "a timed window of a workload that evicts must contain evictions"
+        deferred, spare = deferred_compaction(wl, q_len, variant)
+        # launches that moved rows: every evicting step, or one compaction per spare + 1 steps
+        moved = steps // (spare + 1) * wl.n_layers if deferred else evict_steps2 * wl.n_layers
+        assert not finite or (evict_steps > 0 and pevict == moved > 0), \
+            "a timed window of a workload that evicts must contain its evictions' row moves"
         res = {
             "workload": wl.name,
             "steps_requested": requested,
             "steps_timed": steps,
             "evicting_steps_in_timed_window": evict_steps,
+            "deferred_compaction": bool(deferred and finite),
             "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
             "ms_per_step": gpu_s * 1e3 / steps,
             "wall_ms_per_step": wall_s * 1e3 / steps,

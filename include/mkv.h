@@ -9,8 +9,13 @@
  * lowest-score tokens (Eq. 8) -> removal and compaction (Eq. 9).
  *
  * Conventions
- *   - every function returns MKV_OK (0) or a negative mkv_status; nothing throws or aborts;
- *     on error the cache state is unchanged and mkv_last_error() describes the reason;
+ *   - every function returns MKV_OK (0) or a negative mkv_status; nothing throws or aborts, and
+ *     mkv_last_error() describes the reason.  MKV_ERR_ARG, MKV_ERR_STATE, MKV_ERR_FROZEN,
+ *     MKV_ERR_CAPACITY and MKV_ERR_NOMEM are found before anything is enqueued: the cache state is
+ *     unchanged.  MKV_ERR_HIP from a call that changes the cache (prefill append or compression,
+ *     projection, decode steps, eviction, mkv_load_decode) may come after part of its work was
+ *     enqueued; the context then refuses every further call with MKV_ERR_STATE except
+ *     mkv_destroy;
  *   - "device pointer" = memory of the GPU the context was created on; "host pointer" = ordinary
  *     process memory.  Each argument says which it is;
  *   - the context owns the cache memory (or borrows cfg.arena); the caller owns q/k/v/out;
@@ -71,9 +76,15 @@ typedef struct {
   int32_t evict_trigger;   /* T_e >= B_d: mkv_decode_step evicts back to B_d when the decode pool
                               exceeds T_e.  T_e == B_d is the paper (Alg. 1 "if |pool_d| > B_d").
                               MKV_NEVER_EVICT: only mkv_evict evicts                            */
-  int32_t decode_capacity; /* decode slots per sequence; 0 => evict_trigger + max(1, max_q_len), which
-                              is also the least allowed.  Required (> B_d) with MKV_NEVER_EVICT.
-                              At most 16384                                                     */
+  int32_t decode_capacity; /* decode slots per sequence; at least evict_trigger + max(1, max_q_len), at most
+                              16384; required (> B_d) with MKV_NEVER_EVICT.  0 => that least value, plus
+                              -- at the paper's cadence (evict_trigger == decode_budget) on bf16 layers
+                              with 128-wide heads, max_q_len 0, default attn_variant -- an eighth of the
+                              budget (8..64 slots), which turns on deferred compaction: the token a step
+                              evicts only has its slot marked, attention masks marked slots, and the
+                              rows are compacted when the spare slots are used up (and before any
+                              reader looks).  Results are those of immediate compaction; an explicit
+                              decode_capacity of decode_budget + 1 keeps compaction immediate          */
   int32_t recent_window;   /* W <= B_d: the W newest decode tokens are never evicted.  0 is the
                               paper: Eq. 8 takes its candidates from the whole decode pool      */
   float   alpha;           /* momentum factor in [0, 1] (Eq. 5; the paper uses (0, 1))           */
@@ -134,7 +145,9 @@ int mkv_prefill_compress(mkv_ctx* ctx, int layer, int seq, const float* token_sc
  *                  (the layout of a linear layer's weight), feature = kv_head*head_dim + i
  *   hidden         multiple of 256
  *   rope_positions device pointer int32[batch]: absolute position of the token (prompt length +
- *                  tokens generated so far, as the model counts them)
+ *                  tokens generated so far, as the model counts them), 0 <= position < 2^20; the
+ *                  array lives on the device, so the range is not checked, and beyond it the
+ *                  short argument reduction of the rotation loses accuracy
  *   rope_theta     base of the rotary encoding.  Convention (the paper leaves positional encoding
  *                  to the model): rotate-half -- for i < head_dim/2 and angle pos*theta^(-2i/head_dim),
  *                  (k_i, k_{i+D/2}) -> (k_i cos - k_{i+D/2} sin, k_{i+D/2} cos + k_i sin); v is not rotated.
@@ -232,6 +245,15 @@ int mkv_read_kv(mkv_ctx* ctx, int layer, int seq, int pool, int kv_head, void* k
  * MKV_ERR_STATE if `layer` was not the layer stepped last. */
 int mkv_read_probs(mkv_ctx* ctx, int layer, int seq, float* abar, float* lse_per_head,
                    int capacity, int* n_out);
+
+/* The decode pool of (layer, seq) slot by slot, without compacting it (with deferred compaction the
+ * other readers close the holes first): scores and original positions per slot (host float /
+ * int32 [capacity]), live[j] = 0 where slot j holds a token that has been evicted and awaits
+ * compaction (host uint8 [capacity]); *n_slots = slots in use; *pending_slot = the slot the last
+ * decode step selected for eviction and that is still marked live, or -1.  Any pointer may be NULL.
+ * A context without deferred compaction reports every slot live and nothing pending. */
+int mkv_read_slots(mkv_ctx* ctx, int layer, int seq, float* scores, int32_t* positions, uint8_t* live,
+                   int capacity, int* n_slots, int* pending_slot);
 
 /* MKV_SCORE_PER_KV_HEAD only: selects the KV head whose score vector mkv_read_scores,
  * mkv_write_scores and mkv_read_probs (abar) address from now on (default 0).  mkv_load_decode

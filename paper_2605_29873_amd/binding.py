@@ -22,7 +22,7 @@ MKV_NEVER_EVICT = 2**31 - 1
 
 EXPORTS = ["mkv_required_bytes", "mkv_create", "mkv_destroy", "mkv_prefill_append", "mkv_prefill_compress", "mkv_project_append",
            "mkv_decode_step", "mkv_decode_step_static", "mkv_decode_step_multi", "mkv_evict", "mkv_read_scores", "mkv_write_scores",
-           "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_set_score_view", "mkv_get_lens", "mkv_set_profiling",
+           "mkv_load_decode", "mkv_read_kv", "mkv_read_probs", "mkv_read_slots", "mkv_set_score_view", "mkv_get_lens", "mkv_set_profiling",
            "mkv_read_profile", "mkv_last_error"]
 
 
@@ -73,6 +73,7 @@ def load() -> C.CDLL:
     lib.mkv_load_decode.argtypes = [vp, i32, i32, vp, vp, vp, vp, i32, i64]
     lib.mkv_read_kv.argtypes = [vp, i32, i32, i32, i32, vp, vp, i32, C.POINTER(i32)]
     lib.mkv_read_probs.argtypes = [vp, i32, i32, vp, vp, i32, C.POINTER(i32)]
+    lib.mkv_read_slots.argtypes = [vp, i32, i32, vp, vp, vp, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.mkv_set_score_view.argtypes = [vp, i32]
     lib.mkv_get_lens.argtypes = [vp, i32, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i64)]
     lib.mkv_set_profiling.argtypes = [vp, i32]
@@ -208,6 +209,17 @@ def mkv_read_probs(ctx, layer, seq, n_q_heads, capacity):
     n = C.c_int()
     _check(ctx, load().mkv_read_probs(ctx, layer, seq, a.ctypes.data, lse.ctypes.data, a.size, C.byref(n)))
     return a[:n.value].copy(), lse
+
+
+def mkv_read_slots(ctx, layer, seq, capacity):
+    """Returns (scores float32[n], positions int32[n], live bool[n], pending slot or -1) slot by slot."""
+    s = np.empty(max(capacity, 1), dtype=np.float32)
+    p = np.empty(max(capacity, 1), dtype=np.int32)
+    lv = np.empty(max(capacity, 1), dtype=np.uint8)
+    n, pend = C.c_int(), C.c_int()
+    _check(ctx, load().mkv_read_slots(ctx, layer, seq, s.ctypes.data, p.ctypes.data, lv.ctypes.data, s.size,
+                                      C.byref(n), C.byref(pend)))
+    return s[:n.value].copy(), p[:n.value].copy(), lv[:n.value].astype(bool), pend.value
 
 
 def mkv_set_score_view(ctx, kv_head: int) -> None:

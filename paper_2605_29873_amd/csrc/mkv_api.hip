@@ -10,6 +10,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <mutex>
 #include <new>
 #include <string>
@@ -60,7 +61,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
   // per-layer regions (byte offsets inside a layer block) and the layer stride
-  size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, layer_bytes;
+  size_t Kp, Vp, Kd, Vd, score, pos, mlen, nd, nd_eff, tpos, dead, nholes, pend, layer_bytes;
   // scratch regions (absolute offsets), shared by all layers
   size_t part_o, part_ml, offs, logits, abar, lse, src_map, evict_info, evict_key, total;
   size_t p_score, p_pos, p_map, p_info;   // prompt compression: one sequence at a time
@@ -71,7 +72,30 @@ struct Layout {
   int mq_slot_rows;       // most rows per partial slot on the matrix-core kernels
   bool mfma_single;       // mkv_decode_step runs on the matrix-core kernels
   int pstride, dstride;   // padded row strides of the (seq, kv head) regions
+  bool lazy;              // one-token evictions are deferred: slot bitmap + compaction every few dozen steps
+  int capw;               // words of one score vector's slot bitmap
 };
+
+// Deferred compaction applies at the paper's cadence (trigger == budget: one token leaves per
+// step) on the default matrix-core kernels, single-query steps only.
+bool cadence_on_matrix_cores(const mkv_config* c) {
+  return c->evict_trigger == c->decode_budget && c->max_q_len == 0 && c->dtype == MKV_BF16 &&
+         c->head_dim == 128 && c->attn_variant == 0;
+}
+
+// decode_capacity == 0: one append past the trigger -- plus, where compaction is deferred, room
+// for the evicted tokens' slots between two compactions (an eighth of the budget, 8..64 slots:
+// the dead rows are still streamed by the attention kernel, so the room is kept small).
+int64_t default_capacity(const mkv_config* c) {
+  const int64_t grow = c->max_q_len > 1 ? c->max_q_len : 1;
+  int64_t cap = (int64_t)c->evict_trigger + grow;
+  if (cadence_on_matrix_cores(c)) {
+    int64_t slack = c->decode_budget / 8;
+    slack = slack < 8 ? 8 : slack > 64 ? 64 : slack;
+    if (cap + slack <= kMaxDecodeCapacity) cap += slack;
+  }
+  return cap;
+}
 
 thread_local std::string g_create_error;
 
@@ -115,7 +139,7 @@ std::string check_config(const mkv_config* c) {
   int64_t cap = c->decode_capacity;
   if (cap == 0) {
     if (c->evict_trigger == MKV_NEVER_EVICT) return "decode_capacity is required with MKV_NEVER_EVICT";
-    cap = (int64_t)c->evict_trigger + grow;
+    cap = default_capacity(c);
   }
   if (cap <= c->decode_budget) return "decode_capacity must exceed decode_budget";
   if (c->evict_trigger != MKV_NEVER_EVICT && cap < (int64_t)c->evict_trigger + grow)
@@ -131,7 +155,9 @@ Layout make_layout(const mkv_config* c) {
   const int grow = c->max_q_len > 1 ? c->max_q_len : 1;
   const int G = c->n_q_heads / c->n_kv_heads;
   L.S = c->score_mode == MKV_SCORE_PER_KV_HEAD ? c->n_kv_heads : 1;
-  L.cap = c->decode_capacity ? c->decode_capacity : c->evict_trigger + grow;
+  L.cap = c->decode_capacity ? c->decode_capacity : (int)default_capacity(c);
+  L.lazy = cadence_on_matrix_cores(c) && L.cap > c->decode_budget + 1;
+  L.capw = L.cap / 32 + 2;      // two spare words: a tile's 32 bits are cut out of two consecutive words
   L.HL = head_lanes(G);
   L.passes = (G + L.HL - 1) / L.HL;
   // Single-query steps of bf16 x 128 layers run on the matrix-core kernels as well: the vector-ALU
@@ -170,6 +196,9 @@ Layout make_layout(const mkv_config* c) {
   L.nd = take(B * 4);
   L.nd_eff = take(B * 4);
   L.tpos = take(B * 4);
+  L.dead = take(B * L.S * (size_t)L.capw * 4);
+  L.nholes = take(B * L.S * 4);
+  L.pend = take(2 * B * L.S * 8);       // starts at all ones (no selection pending), the rest at zero
   L.layer_bytes = o;
   o = L.layer_bytes * (size_t)c->n_layers;
   // a work-group takes at least 64 keys, so small pools never need many partial slots
@@ -225,7 +254,11 @@ struct mkv_ctx {
   hipStream_t stream;
   char* arena;
   bool own_arena;
-  std::vector<int32_t> h_mlen, h_nd, h_last_n;  // [L*B]; h_last_n [B]: pool size seen by the last step
+  // [L*B]; h_nd: decode slots in use, of which h_holes hold evicted tokens that await compaction
+  // (deferred compaction only); h_last_n, h_last_slots [B]: live tokens and slots the last step saw
+  std::vector<int32_t> h_mlen, h_nd, h_holes, h_last_n, h_last_slots;
+  std::vector<uint8_t> probs_compacted;  // [B]: compacted since the last step: its per-slot head means are gone
+  bool poisoned;         // a launch failed in the middle of a step: device state and mirror may differ
   std::vector<int64_t> h_step;
   std::vector<uint8_t> frozen;
   std::vector<uint8_t> in_pool;   // [L*B]: mkv_project_append has written the next token's row already
@@ -248,6 +281,17 @@ int fail(mkv_ctx* ctx, int code, const std::string& msg) {
 int fail_hip(mkv_ctx* ctx, hipError_t e, const char* what) {
   return fail(ctx, MKV_ERR_HIP, fmt("%s: %s", what, hipGetErrorString(e)));
 }
+// A HIP error after part of a call's work has been enqueued: the device's bookkeeping and the host
+// mirror may no longer agree, so the context refuses every further call but mkv_destroy.
+int poison(mkv_ctx* ctx, hipError_t e, const char* what) {
+  ctx->poisoned = true;
+  return fail_hip(ctx, e, what);
+}
+// First line of every entry point that uses the cache state.
+int refuse_if_poisoned(mkv_ctx* ctx) {
+  return ctx->poisoned ? fail(ctx, MKV_ERR_STATE, "an earlier call failed half-way (MKV_ERR_HIP): the context can only be destroyed")
+                       : MKV_OK;
+}
 
 LayerView layer_view(const mkv_ctx* c, int layer) {
   char* base = c->arena + c->lay.layer_bytes * (size_t)layer;
@@ -260,6 +304,9 @@ LayerView layer_view(const mkv_ctx* c, int layer) {
   v.nd = (int32_t*)(base + c->lay.nd);
   v.nd_eff = (int32_t*)(base + c->lay.nd_eff);
   v.tpos = (int32_t*)(base + c->lay.tpos);
+  v.dead = (uint32_t*)(base + c->lay.dead);
+  v.nholes = (int32_t*)(base + c->lay.nholes);
+  v.pend = (unsigned long long*)(base + c->lay.pend);
   return v;
 }
 
@@ -341,6 +388,42 @@ int set_device_int(mkv_ctx* c, int32_t* p, int32_t v) {
   return e == hipSuccess ? MKV_OK : fail_hip(c, e, "set_int launch");
 }
 
+// Deferred compaction: closes the holes of the masked sequences that have any (one launch pair for
+// the layer).  Afterwards their slots in use equal their live tokens.
+int flush_holes(mkv_ctx* c, int layer, const SeqMask& mask, const Scratch& sc, const KernelTimer* tm = nullptr,
+                bool* fired = nullptr) {
+  if (fired) *fired = false;
+  if (!c->lay.lazy) return MKV_OK;
+  const int B = c->cfg.batch;
+  SeqMask todo;
+  memset(&todo, 0, sizeof todo);
+  bool any = false;
+  for (int b = 0; b < B; ++b)
+    if (mask.active(b) && c->h_holes[(size_t)layer * B + b] > 0) {
+      todo.w[b >> 6] |= 1ull << (b & 63);
+      any = true;
+    }
+  if (!any) return MKV_OK;
+  hipError_t e = launch_compact_holes(c->shape, layer_view(c, layer), sc, todo, c->stream, tm);
+  if (e != hipSuccess) return poison(c, e, "compaction launch");
+  for (int b = 0; b < B; ++b)
+    if (todo.active(b)) {
+      const size_t i = (size_t)layer * B + b;
+      c->h_nd[i] -= c->h_holes[i];
+      c->h_holes[i] = 0;
+      if (layer == c->last_layer) c->probs_compacted[b] = 1;
+    }
+  if (fired) *fired = true;
+  return MKV_OK;
+}
+
+SeqMask one_seq(int b) {
+  SeqMask m;
+  memset(&m, 0, sizeof m);
+  m.w[b >> 6] |= 1ull << (b & 63);
+  return m;
+}
+
 // Evicts the sequences of `mask` whose mirror length exceeds `threshold`; returns MKV_OK when no
 // sequence qualifies.
 // `selected`: the finishing kernel of the step just taken may have left the one-token selection
@@ -361,7 +444,7 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, const S
   if (!any) return MKV_OK;
   hipError_t e = selected ? launch_evict_one(c->shape, layer_view(c, layer), sc, mask, c->stream, tm)
                           : launch_evict(c->shape, layer_view(c, layer), sc, mask, threshold, c->stream, tm);
-  if (e != hipSuccess) return fail_hip(c, e, "evict launch");
+  if (e != hipSuccess) return poison(c, e, "evict launch");
   for (int b = 0; b < B; ++b) {
     int32_t& n = c->h_nd[(size_t)layer * B + b];
     if (mask.active(b) && n > threshold && n > c->cfg.decode_budget) n = c->cfg.decode_budget;
@@ -376,6 +459,7 @@ int run_evict(mkv_ctx* c, int layer, const SeqMask& mask, int threshold, const S
 int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k_new, const void* v_new,
          void* out, const uint8_t* seq_mask, bool static_scratch = false) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!q || !out) return fail(c, MKV_ERR_ARG, "q and out must not be NULL");
   if ((k_new == nullptr) != (v_new == nullptr)) return fail(c, MKV_ERR_ARG, "k_new and v_new must be given together");
@@ -391,43 +475,29 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     passes = (G + hp - 1) / hp;
   }
   const int P = c->shape.piece_pad;   // positions per unit that stand for the fixed cost of a piece
+  const bool lazy = c->lay.lazy;
+  // 1. checks; nothing is changed before all of them have passed
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
-  InlineLens lens;
-  memset(&lens, 0, sizeof lens);
-  lens.valid = B <= kInlineLens;
-  int n_active = 0, max_n1 = 0;
-  long long total_keys = 0;  // length of the flattened key axis of this launch
+  int n_active = 0;
+  bool need_room = false;              // deferred compaction: some sequence's slots are used up by holes
   for (int b = 0; b < B; ++b) {
-    if (lens.valid) {
-      lens.mlen[b] = c->h_mlen[(size_t)layer * B + b];
-      lens.nd[b] = c->h_nd[(size_t)layer * B + b];
-    }
     if (seq_mask && !seq_mask[b]) continue;
     const size_t i = (size_t)layer * B + b;
     if ((c->in_pool[i] != 0) != rows_in_pool)
       return fail(c, MKV_ERR_STATE, rows_in_pool
                   ? fmt("sequence %d: no row from mkv_project_append is waiting, k_new and v_new are needed", b)
                   : fmt("sequence %d: mkv_project_append has appended this step's row, pass k_new = v_new = NULL", b));
-    if (c->h_nd[i] + q_len > c->lay.cap)
-      return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: %d of %d decode slots used, %d more needed", b,
-                                           c->h_nd[i], c->lay.cap, q_len));
+    if (c->h_nd[i] + q_len > c->lay.cap) {
+      if (c->h_nd[i] - c->h_holes[i] + q_len > c->lay.cap)
+        return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: %d of %d decode slots used, %d more needed", b,
+                                             c->h_nd[i] - c->h_holes[i], c->lay.cap, q_len));
+      need_room = true;
+    }
     mask.w[b >> 6] |= 1ull << (b & 63);
     ++n_active;
-    const int n1 = c->h_nd[i] + q_len;
-    total_keys += (long long)c->cfg.n_kv_heads * passes * (c->h_mlen[i] + n1 + P);
-    if (n1 > max_n1) max_n1 = n1;
   }
   if (n_active == 0) return MKV_OK;
-  if (lens.valid) {
-    long long run = 0;
-    for (int b = 0; b < B; ++b) {
-      lens.offs[b] = run;
-      if (mask.active(b)) run += (long long)c->cfg.n_kv_heads * passes * (lens.mlen[b] + lens.nd[b] + q_len + P);
-    }
-    lens.offs[B] = run;
-  }
-  LayerView lv = layer_view(c, layer);
   hipEvent_t* pe = nullptr;
   KernelTimer t_attn, t_fin, t_ev;
   if (c->prof.on) {
@@ -439,6 +509,49 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     c->prof.evicted[c->prof.used] = 0;
     t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
   }
+  char* static_base = nullptr;
+  if (static_scratch) {
+    hipError_t se = static_scratch_base(&static_base);
+    if (se != hipSuccess) return fail_hip(c, se, "address of the static scratch array");
+  }
+  // 2. deferred compaction: a sequence whose slots are used up gets its holes closed first (the
+  //    live tokens stay what they are; only their slots change)
+  bool timed_evict = false;
+  if (need_room) {
+    Scratch fsc = scratch_view(c);
+    if (static_scratch && carve_static(c, static_base, 0, 1, q_len, &fsc) > kStaticScratchBytes)
+      return fail(c, MKV_ERR_CAPACITY, "the compaction's scratch does not fit the static array: use mkv_decode_step");
+    bool fired = false;
+    int frc = flush_holes(c, layer, mask, fsc, pe ? &t_ev : nullptr, &fired);
+    if (frc != MKV_OK) return frc;
+    timed_evict = fired;
+  }
+  // 3. lengths, flattened key axis
+  InlineLens lens;
+  memset(&lens, 0, sizeof lens);
+  lens.valid = B <= kInlineLens;
+  int max_n1 = 0;
+  long long total_keys = 0;  // length of the flattened key axis of this launch
+  for (int b = 0; b < B; ++b) {
+    const size_t i = (size_t)layer * B + b;
+    if (lens.valid) {
+      lens.mlen[b] = c->h_mlen[i];
+      lens.nd[b] = c->h_nd[i];
+    }
+    if (!mask.active(b)) continue;
+    const int n1 = c->h_nd[i] + q_len;
+    total_keys += (long long)c->cfg.n_kv_heads * passes * (c->h_mlen[i] + n1 + P);
+    if (n1 > max_n1) max_n1 = n1;
+  }
+  if (lens.valid) {
+    long long run = 0;
+    for (int b = 0; b < B; ++b) {
+      lens.offs[b] = run;
+      if (mask.active(b)) run += (long long)c->cfg.n_kv_heads * passes * (lens.mlen[b] + lens.nd[b] + q_len + P);
+    }
+    lens.offs[B] = run;
+  }
+  LayerView lv = layer_view(c, layer);
   // equal key ranges, one per work-group: as many work-groups as the chip holds at once, unless
   // the caller fixed the range length.  The length is not rounded: with sequences of equal length
   // and a unit count that divides (or is divided by) the work-group count, every range then starts
@@ -454,23 +567,20 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   hipError_t e;
   Scratch sc = scratch_view(c);
   if (static_scratch) {
-    char* base = nullptr;
-    e = static_scratch_base(&base);
-    if (e != hipSuccess) return fail_hip(c, e, "address of the static scratch array");
     // partial slots this launch can touch: one per work-group plus one per (sequence, KV head, pass)
     const size_t slots = (size_t)n_groups + (size_t)B * c->cfg.n_kv_heads * passes;
     const int rows = mq ? 16 * mq_row_blocks(G, q_len) : c->lay.HL;
-    const size_t need = carve_static(c, base, slots, rows, q_len, &sc);
+    const size_t need = carve_static(c, static_base, slots, rows, q_len, &sc);
     if (need > kStaticScratchBytes)
       return fail(c, MKV_ERR_CAPACITY, fmt("this step needs %zu bytes of scratch, the static array holds %zu: use "
                                            "mkv_decode_step", need, kStaticScratchBytes));
   }
   if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
-  if (e != hipSuccess) return fail_hip(c, e, "attention launch");
+  if (e != hipSuccess) return poison(c, e, "attention launch");
   if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   else e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
-  if (e != hipSuccess) return fail_hip(c, e, "finish launch");
+  if (e != hipSuccess) return poison(c, e, "finish launch");
   for (int b = 0; b < B; ++b) {
     if (!mask.active(b)) continue;
     const size_t i = (size_t)layer * B + b;
@@ -478,18 +588,40 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     c->h_step[i] += q_len;
     c->frozen[i] = 1;
     c->in_pool[i] = 0;
-    c->h_last_n[b] = c->h_nd[i];
+    c->h_last_n[b] = c->h_nd[i] - c->h_holes[i];
+    c->h_last_slots[b] = c->h_nd[i];
   }
   c->last_layer = layer;
   c->last_q_len = q_len;
   c->last_sc = sc;
+  std::fill(c->probs_compacted.begin(), c->probs_compacted.end(), (uint8_t)0);
   int rc = MKV_OK;
   if (c->cfg.evict_trigger != MKV_NEVER_EVICT) {
     bool fired = false;
-    const bool selected = q_len == 1 && c->cfg.evict_trigger == c->cfg.decode_budget;
-    rc = run_evict(c, layer, mask, c->cfg.evict_trigger, sc, &fired, pe ? &t_ev : nullptr, selected);
-    if (pe && fired) c->prof.evicted[c->prof.used] = 1;
+    if (lazy) {
+      // The finishing kernel has taken the one-token selection of every sequence that holds
+      // budget + 1 live tokens (Eq. 7-8); the token's slot is only marked (Eq. 9 follows at the next
+      // compaction).  Anything further over budget -- possible after mkv_load_decode -- goes
+      // through the general selection, on a pool without holes.
+      bool general = false;
+      for (int b = 0; b < B; ++b) {
+        if (!mask.active(b)) continue;
+        const size_t i = (size_t)layer * B + b;
+        const int live = c->h_nd[i] - c->h_holes[i];
+        if (live == c->cfg.decode_budget + 1) c->h_holes[i] += 1;
+        else if (live > c->cfg.decode_budget) general = true;
+      }
+      if (general) {
+        rc = flush_holes(c, layer, mask, sc);
+        if (rc == MKV_OK) rc = run_evict(c, layer, mask, c->cfg.evict_trigger, sc, &fired, (pe && !timed_evict) ? &t_ev : nullptr, false);
+      }
+    } else {
+      const bool selected = q_len == 1 && c->cfg.evict_trigger == c->cfg.decode_budget;
+      rc = run_evict(c, layer, mask, c->cfg.evict_trigger, sc, &fired, pe ? &t_ev : nullptr, selected);
+    }
+    if (fired) timed_evict = true;
   }
+  if (pe && timed_evict) c->prof.evicted[c->prof.used] = 1;
   if (pe) c->prof.used += 1;
   return rc;
 }
@@ -516,6 +648,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   c->last_layer = -1;
   c->last_q_len = 1;
   c->view = 0;
+  c->poisoned = false;
   if (cfg->arena) {
     if (cfg->arena_bytes < c->lay.total) {
       std::string m = fmt("arena of %zu bytes given, %zu needed", cfg->arena_bytes, c->lay.total);
@@ -544,11 +677,15 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   s.trigger = cfg->evict_trigger; s.S = c->lay.S;
   s.variant = cfg->attn_variant;
   s.piece_pad = kPiecePad;
+  s.lazy = c->lay.lazy ? 1 : 0;
+  s.capw = c->lay.capw;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);
   s.scale_log2 = (float)(scale * 1.4426950408889634074);
   const size_t LB = (size_t)cfg->n_layers * cfg->batch;
-  c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0); c->in_pool.assign(LB, 0);
+  c->h_mlen.assign(LB, 0); c->h_nd.assign(LB, 0); c->h_holes.assign(LB, 0); c->h_step.assign(LB, 0); c->frozen.assign(LB, 0); c->in_pool.assign(LB, 0);
   c->h_last_n.assign(cfg->batch, 0);
+  c->h_last_slots.assign(cfg->batch, 0);
+  c->probs_compacted.assign(cfg->batch, 0);
   c->last_sc = scratch_view(c);
   hipError_t e = configure_kernels();
   if (e == hipSuccess) {   // address of the static scratch array on this GPU, for mkv_decode_step_static
@@ -577,7 +714,9 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   // bookkeeping starts at zero: scores, positions, all lengths, the scratch
   for (int l = 0; l < cfg->n_layers && e == hipSuccess; ++l) {
     char* base = c->arena + c->lay.layer_bytes * (size_t)l;
-    e = hipMemsetAsync(base + c->lay.score, 0, c->lay.layer_bytes - c->lay.score, c->stream);
+    e = hipMemsetAsync(base + c->lay.score, 0, c->lay.pend - c->lay.score, c->stream);
+    if (e == hipSuccess)     // no selection pending: all ones
+      e = hipMemsetAsync(base + c->lay.pend, 0xFF, c->lay.layer_bytes - c->lay.pend, c->stream);
   }
   if (e == hipSuccess)
     e = hipMemsetAsync(c->arena + c->lay.part_o, 0, c->lay.total - c->lay.part_o, c->stream);
@@ -606,6 +745,7 @@ int mkv_destroy(mkv_ctx* c) {
 
 int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void* v, int n_tokens) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   if (n_tokens < 0 || (n_tokens > 0 && (!k || !v))) return fail(c, MKV_ERR_ARG, "k/v NULL or n_tokens < 0");
   if (misaligned(k) || misaligned(v)) return fail(c, MKV_ERR_ARG, "k and v must be 16-byte aligned");
@@ -618,13 +758,14 @@ int mkv_prefill_append(mkv_ctx* c, int layer, int seq, const void* k, const void
   hipError_t e = launch_ingest(c->shape, lv.Kp, lv.Vp, c->lay.pstride, seq, c->h_mlen[i], k, v, n_tokens, c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "ingest launch");
   int rc = set_device_int(c, lv.mlen + seq, c->h_mlen[i] + n_tokens);
-  if (rc != MKV_OK) return rc;
+  if (rc != MKV_OK) { c->poisoned = true; return rc; }    // rows are in the pool, the length is not
   c->h_mlen[i] += n_tokens;
   return MKV_OK;
 }
 
 int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scores, int keep) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   if (!token_scores || keep < 1) return fail(c, MKV_ERR_ARG, "token_scores NULL or keep < 1");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
@@ -638,7 +779,7 @@ int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scor
   // pool: one sequence, one score vector, budget = keep, no protected window.
   Shape s = c->shape;
   s.B = 1; s.S = 1; s.cap = c->cfg.max_prefill; s.dstride = c->lay.pstride;
-  s.budget = keep; s.window = 0; s.trigger = MKV_NEVER_EVICT;
+  s.budget = keep; s.window = 0; s.trigger = MKV_NEVER_EVICT; s.lazy = 0;
   LayerView lv = layer_view(c, layer);
   const size_t rowb = (size_t)c->cfg.head_dim * (c->cfg.dtype == MKV_BF16 ? 2 : 4);
   const size_t seq_off = (size_t)seq * c->cfg.n_kv_heads * c->lay.pstride * rowb;
@@ -662,9 +803,9 @@ int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scor
   memset(&mask, 0, sizeof mask);
   mask.w[0] = 1ull;
   e = launch_evict(s, pv, sc, mask, keep, c->stream);
-  if (e != hipSuccess) return fail_hip(c, e, "prompt compression launch");
+  if (e != hipSuccess) return poison(c, e, "prompt compression launch");
   rc = set_device_int(c, lv.mlen + seq, keep);
-  if (rc != MKV_OK) return rc;
+  if (rc != MKV_OK) { c->poisoned = true; return rc; }
   c->h_mlen[i] = keep;
   return MKV_OK;
 }
@@ -672,6 +813,7 @@ int mkv_prefill_compress(mkv_ctx* c, int layer, int seq, const float* token_scor
 int mkv_project_append(mkv_ctx* c, int layer, const void* x, const void* w_k, const void* w_v, int hidden,
                        const int32_t* rope_positions, float rope_theta, const uint8_t* seq_mask) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (layer < 0 || layer >= c->cfg.n_layers) return fail(c, MKV_ERR_ARG, "layer out of range");
   if (!x || !w_k || !w_v || !rope_positions) return fail(c, MKV_ERR_ARG, "x, w_k, w_v and rope_positions must not be NULL");
   if (misaligned(x) || misaligned(w_k) || misaligned(w_v)) return fail(c, MKV_ERR_ARG, "x, w_k and w_v must be 16-byte aligned");
@@ -682,16 +824,22 @@ int mkv_project_append(mkv_ctx* c, int layer, const void* x, const void* w_k, co
   SeqMask mask;
   memset(&mask, 0, sizeof mask);
   int n_active = 0;
+  bool need_room = false;
   for (int b = 0; b < B; ++b) {
     if (seq_mask && !seq_mask[b]) continue;
     const size_t i = (size_t)layer * B + b;
     if (c->in_pool[i]) return fail(c, MKV_ERR_STATE, fmt("sequence %d: the previous projected row has not been consumed by a decode step", b));
-    if (c->h_nd[i] >= c->lay.cap)
+    if (c->h_nd[i] - c->h_holes[i] >= c->lay.cap)
       return fail(c, MKV_ERR_CAPACITY, fmt("sequence %d: decode pool is full (%d slots)", b, c->lay.cap));
+    if (c->h_nd[i] >= c->lay.cap) need_room = true;
     mask.w[b >> 6] |= 1ull << (b & 63);
     ++n_active;
   }
   if (n_active == 0) return MKV_OK;
+  if (need_room) {       // deferred compaction: the row needs a free slot at the end of the pool
+    int frc = flush_holes(c, layer, mask, scratch_view(c));
+    if (frc != MKV_OK) return frc;
+  }
   hipError_t e = launch_project_append(c->shape, layer_view(c, layer), mask, x, w_k, w_v, rope_positions,
                                        (float*)(c->arena + c->lay.proj_part), hidden, rope_theta, c->stream);
   if (e != hipSuccess) return fail_hip(c, e, "projection launch");
@@ -721,6 +869,7 @@ int mkv_decode_step_multi(mkv_ctx* c, int layer, int q_len, const void* q, const
 
 int mkv_evict(mkv_ctx* c, int layer, int seq) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (layer < 0 || layer >= c->cfg.n_layers || seq < -1 || seq >= c->cfg.batch)
     return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   SeqMask mask;
@@ -731,14 +880,21 @@ int mkv_evict(mkv_ctx* c, int layer, int seq) {
       return fail(c, MKV_ERR_STATE, fmt("sequence %d: a projected row is waiting for its decode step", b));
     mask.w[b >> 6] |= 1ull << (b & 63);
   }
+  int rc = flush_holes(c, layer, mask, scratch_view(c));
+  if (rc != MKV_OK) return rc;
   return run_evict(c, layer, mask, c->cfg.decode_budget, scratch_view(c));
 }
 
 int mkv_read_scores(mkv_ctx* c, int layer, int seq, float* scores, int32_t* positions, int capacity,
                     int* n_out) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
+  {   // readers see the pool in order of generation without holes
+    int frc = flush_holes(c, layer, one_seq(seq), scratch_view(c));
+    if (frc != MKV_OK) return frc;
+  }
   LayerView lv = layer_view(c, layer);
   int32_t n_dev = -1;
   hipError_t e = hipMemcpyAsync(&n_dev, lv.nd + seq, 4, hipMemcpyDeviceToHost, c->stream);
@@ -758,10 +914,15 @@ int mkv_read_scores(mkv_ctx* c, int layer, int seq, float* scores, int32_t* posi
 
 int mkv_write_scores(mkv_ctx* c, int layer, int seq, const float* scores, int n) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq) || !scores) return fail(c, MKV_ERR_ARG, "bad index or NULL scores");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
-  if (n != c->h_nd[i]) return fail(c, MKV_ERR_ARG, fmt("n = %d but the pool holds %d", n, c->h_nd[i]));
+  if (n != c->h_nd[i] - c->h_holes[i]) return fail(c, MKV_ERR_ARG, fmt("n = %d but the pool holds %d", n, c->h_nd[i] - c->h_holes[i]));
   if (n == 0) return MKV_OK;
+  {
+    int frc = flush_holes(c, layer, one_seq(seq), scratch_view(c));
+    if (frc != MKV_OK) return frc;
+  }
   LayerView lv = layer_view(c, layer);
   hipError_t e = hipMemcpyAsync(lv.score + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
   if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
@@ -772,6 +933,7 @@ int mkv_write_scores(mkv_ctx* c, int layer, int seq, const float* scores, int n)
 int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v, const float* scores,
                     const int32_t* positions, int n, int64_t next_step) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   if (n < 0 || (n > 0 && (!k || !v || !scores || !positions))) return fail(c, MKV_ERR_ARG, "NULL input or n < 0");
   if (misaligned(k) || misaligned(v)) return fail(c, MKV_ERR_ARG, "k and v must be 16-byte aligned");
@@ -789,13 +951,21 @@ int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v
     if (e == hipSuccess) e = hipMemcpyAsync(lv.score + vec * c->lay.cap, scores, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
     if (e == hipSuccess) e = hipMemcpyAsync(lv.pos + vec * c->lay.cap, positions, (size_t)n * 4, hipMemcpyHostToDevice, c->stream);
   }
-  if (e != hipSuccess) return fail_hip(c, e, "load decode pool");
+  if (e == hipSuccess && c->lay.lazy) {     // no holes, no selection pending
+    const size_t v0 = (size_t)seq * c->lay.S, half = (size_t)c->cfg.batch * c->lay.S;
+    e = hipMemsetAsync(lv.dead + v0 * c->lay.capw, 0, (size_t)c->lay.S * c->lay.capw * 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(lv.nholes + v0, 0, (size_t)c->lay.S * 4, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(lv.pend + v0, 0xFF, (size_t)c->lay.S * 8, c->stream);
+    if (e == hipSuccess) e = hipMemsetAsync(lv.pend + half + v0, 0xFF, (size_t)c->lay.S * 8, c->stream);
+  }
+  if (e != hipSuccess) return poison(c, e, "load decode pool");
   int rc = set_device_int(c, lv.nd + seq, n);
   if (rc == MKV_OK) rc = set_device_int(c, lv.tpos + seq, (int32_t)next_step);
-  if (rc != MKV_OK) return rc;
+  if (rc != MKV_OK) { c->poisoned = true; return rc; }
   e = hipStreamSynchronize(c->stream);
-  if (e != hipSuccess) return fail_hip(c, e, "load decode pool");
+  if (e != hipSuccess) return poison(c, e, "load decode pool");
   c->h_nd[i] = n;
+  c->h_holes[i] = 0;
   c->h_step[i] = next_step;
   c->frozen[i] = 1;
   c->in_pool[i] = 0;
@@ -805,9 +975,14 @@ int mkv_load_decode(mkv_ctx* c, int layer, int seq, const void* k, const void* v
 int mkv_read_kv(mkv_ctx* c, int layer, int seq, int pool, int kv_head, void* k, void* v, int capacity,
                 int* n_out) {
   if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (bad_index(c, layer, seq) || kv_head < 0 || kv_head >= c->cfg.n_kv_heads || (pool != 0 && pool != 1))
     return fail(c, MKV_ERR_ARG, "bad layer, seq, pool or kv_head");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
+  if (pool == 0) {
+    int frc = flush_holes(c, layer, one_seq(seq), scratch_view(c));
+    if (frc != MKV_OK) return frc;
+  }
   const int n = pool ? c->h_mlen[i] : c->h_nd[i];
   if (n_out) *n_out = n;
   if ((k || v) && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
@@ -828,13 +1003,34 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
                    int* n_out) {
   if (!c) return MKV_ERR_ARG;
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
   if (layer != c->last_layer) return fail(c, MKV_ERR_STATE, "layer was not the layer stepped last");
   const int n = c->h_last_n[seq];
   if (n_out) *n_out = n;
   if (abar && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
   const Scratch& sc = c->last_sc;
   hipError_t e = hipSuccess;
-  if (abar && n) e = hipMemcpyAsync(abar, sc.abar + ((size_t)seq * c->lay.S + c->view) * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  const size_t vec = (size_t)seq * c->lay.S + c->view;
+  const int slots = c->h_last_slots[seq];
+  if (abar && n && slots != n) {
+    // deferred compaction: the step wrote one value per slot; the slots of tokens that had left
+    // before the step are dropped here (the step's own selection was still part of its pool)
+    if (c->probs_compacted[seq])
+      return fail(c, MKV_ERR_STATE, "the pool has been compacted since the step: its head means are gone");
+    std::vector<float> per_slot((size_t)slots);
+    std::vector<uint32_t> dead((size_t)c->lay.capw);
+    e = hipMemcpyAsync(per_slot.data(), sc.abar + vec * c->lay.cap, (size_t)slots * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)
+      e = hipMemcpyAsync(dead.data(), layer_view(c, layer).dead + vec * c->lay.capw, (size_t)c->lay.capw * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "read probs");
+    int k = 0;
+    for (int j = 0; j < slots; ++j)
+      if (!((dead[j >> 5] >> (j & 31)) & 1u) && k < n) abar[k++] = per_slot[j];
+    if (k != n) return fail(c, MKV_ERR_STATE, fmt("%d live slots found, %d expected", k, n));
+  } else if (abar && n) {
+    e = hipMemcpyAsync(abar, sc.abar + vec * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  }
   if (e == hipSuccess && lse_per_head) {
     // [B][q_len][H]: the last query row of the sequence
     const size_t row = (size_t)seq * c->last_q_len + (c->last_q_len - 1);
@@ -844,6 +1040,38 @@ int mkv_read_probs(mkv_ctx* c, int layer, int seq, float* abar, float* lse_per_h
   if (e != hipSuccess) return fail_hip(c, e, "read probs");
   if (lse_per_head)
     for (int h = 0; h < c->cfg.n_q_heads; ++h) lse_per_head[h] *= 0.69314718055994530942f;  // base 2 -> e
+  return MKV_OK;
+}
+
+int mkv_read_slots(mkv_ctx* c, int layer, int seq, float* scores, int32_t* positions, uint8_t* live,
+                   int capacity, int* n_slots, int* pending_slot) {
+  if (!c) return MKV_ERR_ARG;
+  if (refuse_if_poisoned(c)) return MKV_ERR_STATE;
+  if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
+  const size_t i = (size_t)layer * c->cfg.batch + seq;
+  const int n = c->h_nd[i];
+  if (n_slots) *n_slots = n;
+  if (pending_slot) *pending_slot = -1;
+  if ((scores || positions || live) && capacity < n) return fail(c, MKV_ERR_CAPACITY, "buffer too small");
+  LayerView lv = layer_view(c, layer);
+  const size_t vec = (size_t)seq * c->lay.S + c->view;
+  hipError_t e = hipSuccess;
+  std::vector<uint32_t> dead;
+  unsigned long long pend = ~0ull;
+  if (scores && n) e = hipMemcpyAsync(scores, lv.score + vec * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && positions && n)
+    e = hipMemcpyAsync(positions, lv.pos + vec * c->lay.cap, (size_t)n * 4, hipMemcpyDeviceToHost, c->stream);
+  if (e == hipSuccess && c->lay.lazy) {
+    dead.resize((size_t)c->lay.capw);
+    e = hipMemcpyAsync(dead.data(), lv.dead + vec * c->lay.capw, (size_t)c->lay.capw * 4, hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess)    // the half that belongs to a pool of n slots
+      e = hipMemcpyAsync(&pend, lv.pend + (size_t)(n & 1) * c->cfg.batch * c->lay.S + vec, 8, hipMemcpyDeviceToHost, c->stream);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return fail_hip(c, e, "read slots");
+  if (live)
+    for (int j = 0; j < n; ++j) live[j] = dead.empty() ? 1 : !((dead[j >> 5] >> (j & 31)) & 1u);
+  if (pending_slot && pend != ~0ull) *pending_slot = (int)(uint32_t)pend;
   return MKV_OK;
 }
 
@@ -859,7 +1087,7 @@ int mkv_get_lens(mkv_ctx* c, int layer, int seq, int* n_prefill, int* n_decode, 
   if (bad_index(c, layer, seq)) return fail(c, MKV_ERR_ARG, "layer or seq out of range");
   const size_t i = (size_t)layer * c->cfg.batch + seq;
   if (n_prefill) *n_prefill = c->h_mlen[i];
-  if (n_decode) *n_decode = c->h_nd[i];
+  if (n_decode) *n_decode = c->h_nd[i] - c->h_holes[i];
   if (step) *step = c->h_step[i];
   return MKV_OK;
 }

@@ -95,7 +95,13 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 //
 // NB: row blocks of 16 per pass.  With heads x query positions above 16 a pass carries two blocks
 // (32 rows): every K and V tile is then used twice, instead of reading the pool in two passes.
-template <int WPB, int AUXK, int AUXV, int NB>
+//
+// LAZY (deferred compaction, Shape::lazy): decode slots whose token has been evicted still hold
+// their rows.  A tile of pool keys comes with the 32 bits of the vector's slot bitmap that cover
+// it, and the slot picked by the previous step's selection is compared by value; such keys are
+// masked like keys past the end of the segment.  Work-group 0 moves that pending slot into the
+// bitmap and clears the half of `pend` that this step's finishing kernel will write.
+template <int WPB, int AUXK, int AUXV, int NB, bool LAZY>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   constexpr int kRows = 16 * NB;         // rows of a pass = rows of a partial slot
   constexpr int kThreads = WPB * 64;
@@ -120,8 +126,25 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     for (int b = tid; b <= s.B; b += kThreads) {
       a.sc.offs[b] = offs[b];
       if (b < s.B && a.mask.active(b)) {
-        a.lv.nd_eff[b] = (a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b]) + Q;
+        const int nb0 = a.lens.valid ? a.lens.nd[b & (kInlineLens - 1)] : a.lv.nd[b];
+        a.lv.nd_eff[b] = nb0 + Q;
         for (int sv = 0; sv < s.S; ++sv) a.sc.evict_key[b * s.S + sv] = ~0ull;   // this step's selection may land here
+        if constexpr (LAZY) {
+          for (int sv = 0; sv < s.S; ++sv) {
+            const int vec = b * s.S + sv;
+            const unsigned long long p = a.lv.pend[(size_t)(nb0 & 1) * s.B * s.S + vec];
+            if (p != ~0ull) {            // the slot the previous step selected joins the bitmap (once)
+              const uint32_t slot = (uint32_t)p;
+              uint32_t* w = a.lv.dead + (size_t)vec * s.capw + (slot >> 5);
+              const uint32_t old = *w;
+              if (!((old >> (slot & 31)) & 1u)) {
+                *w = old | (1u << (slot & 31));
+                a.lv.nholes[vec] += 1;
+              }
+            }
+            a.lv.pend[(size_t)((nb0 + 1) & 1) * s.B * s.S + vec] = ~0ull;
+          }
+        }
       }
     }
   }
@@ -181,6 +204,16 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int WT = SK / kTK;
     const int SKP = SK + 4;
 
+    // deferred compaction: the bitmap of the score vector that governs this KV head, and the slot
+    // the previous step selected (-1: none)
+    [[maybe_unused]] const uint32_t* deadw = nullptr;
+    [[maybe_unused]] int pend_slot = -1;
+    if constexpr (LAZY) {
+      const int vec = b * s.S + (s.S > 1 ? g : 0);
+      deadw = a.lv.dead + (size_t)vec * s.capw;
+      const unsigned long long p = a.lv.pend[(size_t)(n0 & 1) * s.B * s.S + vec];
+      pend_slot = uniform(p == ~0ull ? -1 : (int)(uint32_t)p);
+    }
     const size_t head_row = (size_t)uniform(b * s.Hkv + g);
     const char* kpre = (const char*)a.lv.Kp + head_row * (size_t)s.pstride * kRowB;
     const char* vpre = (const char*)a.lv.Vp + head_row * (size_t)s.pstride * kRowB;
@@ -270,6 +303,21 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       t.vv = pick(seg == 2, vv_new, vv_pool);
       return t;
     };
+    // the 32 bitmap bits of a tile of pool keys (bit i: key i of the tile is an evicted slot); the
+    // load is unconditional like the others (word 0 for tiles that need none)
+    auto load_dead = [&](int tt, int t_end) __attribute__((always_inline)) {
+      if constexpr (!LAZY) return 0u;
+      else {
+        const int seg = tile_seg(tt);
+        const int jb = tile_key(tt, seg);
+        const bool pool_tile = seg == 1 && tt < t_end;
+        const int wi = pool_tile ? (jb >> 5) : 0;
+        const uint32_t w0 = deadw[wi], w1 = deadw[wi + 1];     // the bitmap has two spare words
+        const uint32_t sh = (uint32_t)jb & 31u;
+        const uint32_t m = sh ? ((w0 >> sh) | (w1 << (32u - sh))) : w0;
+        return pool_tile ? m : 0u;
+      }
+    };
     auto load_k = [&](int tt, int t_end, uint4 (&kr)[2][4]) __attribute__((always_inline)) {
       const TileAddr t = tile_addr(tt, t_end);
 #pragma unroll
@@ -293,7 +341,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     constexpr float kSlack = 8.0f;
     // scores of one tile against the rows of each block: x[nb][4h + i] = logit of key 16h + 4j + i (base 2), -inf
     // where masked; decode logits are staged for the score update
-    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], float (&x)[NB][8]) __attribute__((always_inline)) {
+    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], uint32_t dmask, float (&x)[NB][8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
       const int jn = pick3(seg, p1, dp, d1);
@@ -317,7 +365,9 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
           for (int i = 0; i < 4; ++i) {
             const int key = key0 + i;
             // past the segment, or an appended token that comes after this row's own (causal order)
-            const bool ok = key < jn && !(seg == 2 && key - n0 > qi[nb]);
+            bool ok = key < jn && !(seg == 2 && key - n0 > qi[nb]);
+            if constexpr (LAZY)      // an evicted slot that still holds its rows
+              ok = ok && !(seg == 1 && (((dmask >> (16 * h + 4 * j4 + i)) & 1u) || key == pend_slot));
             x[nb][4 * h + i] = ok ? sx[i] : -INFINITY;
           }
         }
@@ -388,11 +438,13 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     auto run_tiles = [&](int t_lo, int t_hi) __attribute__((always_inline)) {
       uint4 kbuf[2][4], vbuf[2][4];
       int tt = t_lo + wave;
+      uint32_t dmask = load_dead(tt, t_hi);
       load_k(tt, t_hi, kbuf);
       load_v(tt, t_hi, vbuf);
       while (tt < t_hi) {
         float x[NB][8];
-        score_tile(tt, kbuf, x);
+        score_tile(tt, kbuf, dmask, x);
+        dmask = load_dead(tt + WPB, t_hi);
         load_k(tt + WPB, t_hi, kbuf);
         PairB pb[NB];
 #pragma unroll
@@ -612,6 +664,11 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   float xpre[kPre];
   constexpr int kPreS = 8;               // score vectors whose previous value is fetched up front too
   float ipre[kPreS];
+  // deferred compaction: the word of each vector's slot bitmap that holds this slot's bit
+  uint32_t dpre[kPreS];
+#pragma unroll
+  for (int sv = 0; sv < kPreS; ++sv)
+    dpre[sv] = (s.lazy && sv < s.S && j < n1) ? a.lv.dead[((size_t)b * s.S + sv) * s.capw + (j >> 5)] : 0u;
   if (j < n1) {
     if constexpr (ONE) {
       const float* lg0 = a.sc.logits + logit_index(s, b, rows, 0, j);
@@ -671,10 +728,12 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       __syncthreads();
     }
   }
-  // One token appended and exactly one to evict (trigger = budget, pool at budget + 1): the
-  // selection of Eq. 8 is an arg-min over the scores computed right here; every slot block merges
-  // its candidates' minimum into the vector's evict_key.
-  const bool pick_one = Q == 1 && s.trigger == s.budget && n1 == s.budget + 1;
+  // One token appended and exactly one to evict (trigger = budget, pool at budget + 1 live
+  // tokens): the selection of Eq. 8 is an arg-min over the scores computed right here; every slot
+  // block merges its candidates' minimum into the vector's selection key -- evict_key for the row
+  // shift that follows, or, with deferred compaction, the half of `pend` that belongs to a pool of
+  // n1 slots.
+  const bool one_out = Q == 1 && s.trigger == s.budget;
   // One score vector per sequence (mean over all H heads, Eq. 4 as printed) or one per KV head
   // (mean over the G heads of the group): vector sv covers heads [sv*Hs, (sv+1)*Hs).
   const int Hs = s.H / s.S;
@@ -685,14 +744,24 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   for (int sv = 0; sv < s.S; ++sv) {
     unsigned long long key = ~0ull;
     const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
+    const int vec = b * s.S + sv;
+    const bool pick_one = one_out && n1 - (s.lazy ? a.lv.nholes[vec] : 0) == s.budget + 1;
+    unsigned long long* key_dst = s.lazy ? a.lv.pend + (size_t)(n1 & 1) * s.B * s.S + vec : a.sc.evict_key + vec;
     float I = 0.f;                       // previous score of the slot (0 for one appended now, Eq. 6)
+    uint32_t dword = 0u;
     if (sv < kPreS) {
       I = ipre[0];
+      dword = dpre[0];
 #pragma unroll
-      for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
-    } else if (j < n0) {
-      I = a.lv.score[si];
+      for (int u = 1; u < kPreS; ++u) {
+        I = (sv == u) ? ipre[u] : I;
+        dword = (sv == u) ? dpre[u] : dword;
+      }
+    } else if (j < n1) {
+      if (j < n0) I = a.lv.score[si];
+      if (s.lazy) dword = a.lv.dead[(size_t)vec * s.capw + (j >> 5)];
     }
+    const bool alive = !((dword >> (j & 31)) & 1u);   // an evicted slot takes no update and is no candidate
     if constexpr (ONE) {
       if (j < n1) {
         float sum0 = 0.f, sum1 = 0.f;
@@ -701,11 +770,11 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
           if (h >= sv * Hs && h < (sv + 1) * Hs) sum0 += fast_exp2(xpre[h] - smem[h]);
           if (h + 1 >= sv * Hs && h + 1 < (sv + 1) * Hs) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
         }
-        const float abar = (sum0 + sum1) * inv_Hs;
+        const float abar = alive ? (sum0 + sum1) * inv_Hs : 0.f;
         I = fmaf(s.alpha, I, abar);
-        a.lv.score[si] = I;
+        if (alive) a.lv.score[si] = I;
         a.sc.abar[si] = abar;
-        if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+        if (pick_one && alive && j < n1 - s.window) key = evict_key_of(I, j);
       }
     } else {
       // Head means first, the recurrence after: wave w forms abar of query rows w, w+4, ... for
@@ -759,19 +828,19 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
           abar = sm_abar[qi][lane];
           I = fmaf(s.alpha, I, abar);    // Eq. 5
         }
-        a.lv.score[si] = I;
-        a.sc.abar[si] = abar;
-        if (pick_one && j < n1 - s.window) key = evict_key_of(I, j);
+        if (alive) a.lv.score[si] = I;
+        a.sc.abar[si] = alive ? abar : 0.f;
+        if (pick_one && alive && j < n1 - s.window) key = evict_key_of(I, j);
       }
       if (sv + 1 < s.S) __syncthreads();   // the next vector reuses sm_abar
     }
-    if (pick_one) block_min_key_to(key, a.sc.evict_key + b * s.S + sv, key_slots, tid);
+    if (pick_one) block_min_key_to(key, key_dst, key_slots, tid);
   }
 }
 
-template <int WPB, int AUXK = 0, int AUXV = 0, int NB = 1>
+template <int WPB, int AUXK = 0, int AUXV = 0, int NB = 1, bool LAZY = false>
 hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  auto kern = attn_mq_kernel<WPB, AUXK, AUXV, NB>;
+  auto kern = attn_mq_kernel<WPB, AUXK, AUXV, NB, LAZY>;
   if (occupancy) return hipOccupancyMaxActiveBlocksPerMultiprocessor(occupancy, kern, WPB * 64, 0);
   if (tm) hipExtLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, a);
@@ -790,6 +859,7 @@ hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_
   // (measured traffic +2.5 %).  Llama-shaped layers: 72 -> 64 us (420 MB), 460 -> 418 us (2.7 GB
   // per layer); neutral on a pool that fits the on-package cache.  Hint on K only or on both: worse.
   if (a.s.variant == 20) return launch_mq_w<8, 0, 0>(a, n_groups, occupancy, st, tm);
+  if (a.s.lazy) return launch_mq_w<8, 0, 2, 1, true>(a, n_groups, occupancy, st, tm);   // the host sets lazy for the default variant only
   return launch_mq_w<8, 0, 2>(a, n_groups, occupancy, st, tm);
 }
 

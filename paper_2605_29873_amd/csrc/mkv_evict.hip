@@ -190,6 +190,72 @@ __global__ __launch_bounds__(kSelThreads) void evict_select_kernel(const EvictAr
   }
 }
 
+// Deferred compaction (Shape::lazy): the tokens that left are known already -- the bits of the
+// vector's slot bitmap plus the selection of the last step, which has not reached the bitmap yet
+// -- so this is the second half of the selection kernel alone: keep flags, prefix sum, scores and
+// positions rewritten from LDS, the new-slot -> old-slot map for the row mover.  Clears the bitmap,
+// the hole count and both halves of the pending selection.  One work-group per score vector.
+__global__ __launch_bounds__(kSelThreads) void compact_holes_kernel(const EvictArgs a) {
+  const Shape& s = a.s;
+  const int vec = blockIdx.x;
+  const int b = vec / s.S;
+  if (!a.mask.active(b)) return;
+  const int tid = threadIdx.x;
+  const int n = a.lv.nd[b];
+  int* info = a.sc.evict_info + 2 * vec;
+  uint32_t* dead = a.lv.dead + (size_t)vec * s.capw;
+  const size_t half = (size_t)s.B * s.S;
+  const unsigned long long p = a.lv.pend[(size_t)(n & 1) * half + vec];
+  const int pslot = p == ~0ull ? -1 : (int)(uint32_t)p;
+  if (a.lv.nholes[vec] == 0 && pslot < 0) {   // nothing to close (the same for every thread)
+    if (tid == 0) { info[0] = n; info[1] = n; }
+    return;
+  }
+  extern __shared__ uint32_t smem[];
+  uint32_t* raw = smem;                       // [cap] score bits
+  int32_t* posl = (int32_t*)(smem + s.cap);   // [cap]
+  __shared__ int sh_first;
+  __shared__ int wave_sums[kSelWaves];
+  float* score = a.lv.score + (size_t)vec * s.cap;
+  int32_t* pos = a.lv.pos + (size_t)vec * s.cap;
+  for (int j = tid; j < n; j += kSelThreads) {
+    raw[j] = __builtin_bit_cast(uint32_t, score[j]);
+    posl[j] = pos[j];
+  }
+  if (tid == 0) sh_first = n;
+  const int items = (n + kSelThreads - 1) / kSelThreads;   // contiguous slots per thread: sums follow slot order
+  const int jb = tid * items;
+  const int je = min(n, jb + items);
+  int keep_cnt = 0;
+  uint64_t evict_bits = 0;                    // items <= 16 by the capacity limit
+  for (int j = jb; j < je; ++j) {
+    const bool ev = ((dead[j >> 5] >> (j & 31)) & 1u) || j == pslot;
+    if (ev) evict_bits |= 1ull << (j - jb);
+    else ++keep_cnt;
+  }
+  int total;
+  int dst = block_excl_scan(keep_cnt, wave_sums, &total);   // (its barriers also publish raw, posl, sh_first)
+  int first = n;
+  int32_t* map = a.sc.src_map + (size_t)vec * s.cap;
+  for (int j = jb; j < je; ++j) {
+    if ((evict_bits >> (j - jb)) & 1ull) { first = min(first, j); continue; }
+    map[dst] = j;
+    score[dst] = __builtin_bit_cast(float, raw[j]);
+    pos[dst] = posl[j];
+    ++dst;
+  }
+  if (first < n) atomicMin(&sh_first, first);
+  __syncthreads();                            // every thread has read its bitmap words
+  for (int w = tid; w < s.capw; w += kSelThreads) dead[w] = 0u;
+  if (tid == 0) {
+    a.lv.nholes[vec] = 0;
+    a.lv.pend[vec] = ~0ull;
+    a.lv.pend[half + vec] = ~0ull;
+    info[0] = sh_first;   // slots below the first hole stay where they are
+    info[1] = total;      // live tokens; published as the pool size by the row mover
+  }
+}
+
 constexpr int kMoveThreads = 1024;
 constexpr int kSliceBytes = 128;
 // 16 bytes in flight between a round's reads and its writes.  A native vector, not HIP's uint4
@@ -330,9 +396,11 @@ __global__ void ingest_kernel(char* Kpool, char* Vpool, const char* k, const cha
 
 hipError_t configure_kernels() {
   // the selection keeps scores + positions of one pool in LDS: up to 128 KiB of the CU's 160 KiB
-  return hipFuncSetAttribute((const void*)evict_select_kernel,
-                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                             kMaxDecodeCapacity * 8);
+  hipError_t e = hipFuncSetAttribute((const void*)evict_select_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeCapacity * 8);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute((const void*)compact_holes_kernel,
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaxDecodeCapacity * 8);
 }
 
 hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
@@ -343,6 +411,24 @@ hipError_t launch_evict(const Shape& s, const LayerView& lv, const Scratch& sc, 
   // with a timer: start is taken at the selection kernel, stop after the row mover
   if (tm) hipExtLaunchKernelGGL(evict_select_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, tm->start, nullptr, 0, a);
   else hipLaunchKernelGGL(evict_select_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int rowb = s.D * (s.bf16 ? 2 : 4);
+  constexpr int kRowsPerPass = kMoveThreads / (kSliceBytes / 16);
+  auto kern = s.budget <= kRowsPerPass * 8 ? evict_move_kernel<8> : evict_move_kernel<1>;
+  const dim3 grid(rowb / kSliceBytes, s.Hkv * 2, s.B);
+  if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, nullptr, tm->stop, 0, a, rowb);
+  else hipLaunchKernelGGL(kern, grid, dim3(kMoveThreads), 0, st, a, rowb);
+  return hipGetLastError();
+}
+
+hipError_t launch_compact_holes(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                                hipStream_t st, const KernelTimer* tm) {
+  EvictArgs a;
+  a.s = s; a.lv = lv; a.sc = sc; a.mask = mask; a.threshold = s.budget;
+  const size_t smem = (size_t)s.cap * 8;
+  if (tm) hipExtLaunchKernelGGL(compact_holes_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, tm->start, nullptr, 0, a);
+  else hipLaunchKernelGGL(compact_holes_kernel, dim3(s.B * s.S), dim3(kSelThreads), smem, st, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int rowb = s.D * (s.bf16 ? 2 : 4);

@@ -41,6 +41,9 @@ struct Shape {
   int trigger;       // the decode step evicts when the pool exceeds this (INT32_MAX: never)
   int variant;       // attention kernel variant (tuning), 0 = default
   int piece_pad;     // positions of the flattened key axis charged to a unit for starting a piece
+  int lazy;          // 1: one-token evictions only mark the slot (LayerView::dead) and the rows are
+                     //    compacted every few dozen steps; 0: every eviction compacts at once
+  int capw;          // 32-bit words of one score vector's slot bitmap (LayerView::dead)
   float alpha;
   float scale_log2;  // softmax scale * log2(e): logits are kept in base-2 units
 };
@@ -56,6 +59,14 @@ struct LayerView {
   int32_t* nd;             // [B]        decode pool size before the step in flight
   int32_t* nd_eff;         // [B]        decode pool size including the token appended in this step
   int32_t* tpos;           // [B]        decode steps taken = position the next token gets
+  // Deferred compaction (Shape::lazy).  A slot whose token has been evicted keeps its rows until
+  // the next compaction; the attention kernel masks it, the finishing kernel skips it.
+  uint32_t* dead;          // [B][S][capw]  bit j set: slot j holds an evicted token
+  int32_t* nholes;         // [B][S]        number of bits set in the vector's bitmap
+  // [2][B][S]: selection key (score key, slot) of the one-token eviction taken by the step that
+  // brought the pool to n slots sits in half n & 1 (~0: none).  The next step's attention kernel
+  // masks that slot and moves it into the bitmap.
+  unsigned long long* pend;
 };
 
 // Per-step scratch, shared by all layers (layers run one after another on one stream).
@@ -110,6 +121,11 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
                             hipStream_t st, const KernelTimer* tm = nullptr);
+
+// Compaction of the slots marked in LayerView::dead (plus the pending selection) for the masked
+// sequences: survivors move down in order, the bitmaps are cleared, nd becomes the live count.
+hipError_t launch_compact_holes(const Shape& s, const LayerView& lv, const Scratch& sc, const SeqMask& mask,
+                                hipStream_t st, const KernelTimer* tm = nullptr);
 
 // One-token eviction of the sequences whose evict_key is set, all of which hold budget + 1 tokens:
 // the selection was made by the finishing kernel, this only closes the gap.

@@ -57,6 +57,10 @@ __device__ __forceinline__ uint16_t f64_to_bf16_rne(double x) {
 // |k| < 2^20), then the usual minimax polynomials on [-pi/4, pi/4].  A few dozen double FMAs; the
 // library routine with its large-argument path costs an order of magnitude more, and the double
 // unit is what this kernel's epilogue waits for.
+// Provenance of the constants: the three-part split of pi/2 (33 + 33 + 53 bits), 2/pi and the
+// minimax coefficients S1..S6 / C1..C6 are those of the public-domain fdlibm routines
+// (e_rem_pio2.c, k_sin.c, k_cos.c; Sun Microsystems, 1993), the table every libm derives from;
+// the code around them is this file's own.
 __device__ __forceinline__ void sincos_small(double x, double* sn, double* cs) {
   const double k = rint(x * 6.36619772367581382433e-01);          // x * 2/pi
   double r = fma(-k, 1.57079632673412561417e+00, x);               // pi/2, first 33 bits

@@ -531,3 +531,143 @@ class FreeRun:
                         keep = expect[vec][2]
                         assert np.array_equal(rows_a[g][0], rows_before[g][0][keep])
                         assert np.array_equal(rows_a[g][1], rows_before[g][1][keep])
+
+
+class DeferredRun:
+    """A context that evicts by itself at the paper's cadence with deferred compaction (the
+    token a step evicts only has its slot marked; rows are compacted every few dozen steps),
+    followed by the oracle without score injection.
+
+    mkv_read_slots shows the pool slot by slot without compacting it: after a step the selected
+    slot is still marked live and keeps its score, so the float32 scores the device selected on are
+    all there.  The oracle's selection (Eq. 8) on those bits must name exactly the pending slot;
+    the oracle's own float64 run is compared at the score tolerance every step, near-ties between
+    the two selections are counted and the oracle then removes the device's token.  Every
+    `read_every` steps the ordinary readers are used as well (they compact first): positions,
+    scores and rows must be the oracle's pool."""
+
+    def __init__(self, mkv, wl: X.Workload, seqs=None, active=None, per_head: bool = False,
+                 decode_capacity: int = 0, split_keys: int = 0, static_scratch: bool = False):
+        self.mkv, self.wl, self.per_head = mkv, wl, per_head
+        self.seqs = list(range(wl.batch)) if seqs is None else list(seqs)
+        self.active = list(self.seqs) if active is None else list(active)
+        mode = mkv.MKV_SCORE_PER_KV_HEAD if per_head else mkv.MKV_SCORE_LAYER_MEAN
+        self.ctx = make_ctx(mkv, wl, manual_evict=False, split_keys=split_keys, score_mode=mode,
+                            decode_capacity=decode_capacity)
+        self.n_vec = wl.n_kv_heads if per_head else 1
+        self.oracles = {s: oracle_state(wl, "per_kv_head" if per_head else "layer_mean") for s in self.seqs}
+        tdt = torch.bfloat16 if wl.dtype == "bf16" else torch.float32
+        self.out = torch.zeros((wl.batch, wl.n_q_heads, wl.head_dim), dtype=tdt, device="cuda")
+        self.mask = np.zeros(wl.batch, dtype=np.uint8)
+        self.mask[self.active] = 1
+        self.dt = mkv.MKV_BF16 if wl.dtype == "bf16" else mkv.MKV_F32
+        self.step_fn = mkv.mkv_decode_step_static if static_scratch else mkv.mkv_decode_step
+        self.max_out_err = self.max_score_rel = 0.0
+        self.evictions = self.near_ties = 0
+        self.max_holes = 0
+        self.evicted_slots = []
+        self.cap_seen = 0
+
+    def close(self):
+        if self.ctx:
+            self.mkv.mkv_destroy(self.ctx)
+            self.ctx = None
+
+    def prefill(self):
+        wl = self.wl
+        for s in self.active:
+            k, v = X.prefill_kv(wl, 0, s)
+            if k.shape[0]:
+                dk, dv = to_device(k, wl.dtype), to_device(v, wl.dtype)
+                self.mkv.mkv_prefill_append(self.ctx, 0, s, dk.data_ptr(), dv.data_ptr(), k.shape[0])
+            if s in self.oracles:
+                self.oracles[s].prefill_append(k, v)
+        torch.cuda.synchronize()
+
+    def load_snapshot(self, n_d: int, t_now: int):
+        assert not self.per_head
+        for s in self.active:
+            k, v, sc, pos = X.decode_snapshot(self.wl, 0, s, n_d, t_now)
+            dk, dv = to_device(k, self.wl.dtype), to_device(v, self.wl.dtype)
+            self.mkv.mkv_load_decode(self.ctx, 0, s, dk.data_ptr(), dv.data_ptr(), sc, pos, t_now)
+            if s in self.oracles:
+                self.oracles[s].load_decode(k, v, sc, pos, t_now)
+
+    def step(self, t: int, read: bool = False, check_abar: bool = False):
+        wl, mkv = self.wl, self.mkv
+        q, k, v = X.step_batch(wl, 0, t)
+        dq, dk, dv = (to_device(a, wl.dtype) for a in (q, k, v))
+        self.step_fn(self.ctx, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), self.out.data_ptr(), self.mask)
+        torch.cuda.synchronize()
+        got = from_device(self.out)
+        rtol, atol = OUT_TOL[wl.dtype]
+        cap = 16384
+        for s in self.seqs:
+            st = self.oracles[s]
+            ref, abar = st.decode_step(q[s], k[s], v[s], auto_evict=False)
+            err = np.abs(got[s] - ref)
+            self.max_out_err = max(self.max_out_err, float(err.max()))
+            assert np.all(err <= atol + rtol * np.abs(ref)), f"step {t} seq {s}: attention output off by {err.max():.3e}"
+            fire = st.n_decode > wl.evict_trigger
+            assert st.n_decode <= wl.decode_budget + 1, "the cadence keeps the pool at budget + 1 before an eviction"
+            expect = []
+            for vec in range(self.n_vec):
+                if self.per_head:
+                    mkv.mkv_set_score_view(self.ctx, vec)
+                S, P, live, pend = mkv.mkv_read_slots(self.ctx, 0, s, cap)
+                self.max_holes = max(self.max_holes, int((~live).sum()))
+                self.cap_seen = max(self.cap_seen, S.size)
+                idx = np.nonzero(live)[0]
+                assert np.array_equal(P[idx], st.pos[vec].astype(np.int32)), f"step {t} seq {s} vec {vec}: live positions differ"
+                ref_I = st.I[vec]
+                e = np.abs(S[idx].astype(np.float64) - ref_I)
+                self.max_score_rel = max(self.max_score_rel, float(np.max(e / (np.abs(ref_I) + 1e-30))))
+                assert np.all(e <= SCORE_RTOL * np.abs(ref_I) + SCORE_ATOL), \
+                    f"step {t} seq {s} vec {vec}: score mismatch, worst rel {np.max(e / (np.abs(ref_I) + 1e-30)):.3e}"
+                if check_abar:
+                    ga, _ = mkv.mkv_read_probs(self.ctx, 0, s, wl.n_q_heads, cap)
+                    a_ref = abar[vec] if self.per_head else abar
+                    assert ga.shape == a_ref.shape
+                    assert np.all(np.abs(ga - a_ref) <= SCORE_RTOL * a_ref + SCORE_ATOL), f"step {t} seq {s}: abar mismatch"
+                if not fire:
+                    assert pend == -1, f"step {t} seq {s} vec {vec}: a selection is pending though the pool is within budget"
+                    expect.append((S[idx], P[idx]))
+                    continue
+                E_g = O.select_evict(S[idx], P[idx], 1, wl.recent_window)          # Eq. 8 on the device's bits
+                assert pend == idx[E_g[0]], \
+                    f"step {t} seq {s} vec {vec}: device selected slot {pend}, the oracle's rule on the same scores slot {idx[E_g[0]]}"
+                E_o = O.select_evict(ref_I.astype(np.float32), st.pos[vec], 1, wl.recent_window)
+                if not np.array_equal(E_g, E_o):
+                    both = np.array([E_g[0], E_o[0]])
+                    cut = float(S[idx][E_g[0]])
+                    slack = 2 * (SCORE_RTOL * abs(cut) + SCORE_ATOL)
+                    assert np.all(np.abs(S[idx][both] - cut) <= slack) and np.all(np.abs(ref_I[both] - cut) <= 2 * slack), \
+                        f"step {t} seq {s} vec {vec}: selections differ beyond a near-tie"
+                    self.near_ties += 1
+                st.remove(vec, E_g)
+                self.evicted_slots.append(int(pend))
+                keep = O.survivors(idx.size, E_g)
+                expect.append((S[idx][keep], P[idx][keep]))
+            if fire:
+                self.evictions += 1
+            if read:
+                for vec in range(self.n_vec):
+                    if self.per_head:
+                        mkv.mkv_set_score_view(self.ctx, vec)
+                    gs, gp = mkv.mkv_read_scores(self.ctx, 0, s)      # compacts first
+                    assert np.array_equal(gp, expect[vec][1]), f"step {t} seq {s} vec {vec}: compacted positions differ"
+                    assert np.array_equal(gs.view(np.uint32), expect[vec][0].view(np.uint32)), \
+                        f"step {t} seq {s} vec {vec}: compacted scores differ"
+                    S2, P2, live2, pend2 = mkv.mkv_read_slots(self.ctx, 0, s, cap)
+                    assert live2.all() and pend2 == -1 and np.array_equal(P2, gp)
+                assert mkv.mkv_get_lens(self.ctx, 0, s)[1] == st.n_decode
+                for g in range(wl.n_kv_heads):
+                    kk, vv = mkv.mkv_read_kv(self.ctx, 0, s, 0, g, wl.head_dim, self.dt)
+                    vec = g if self.per_head else 0
+                    col = 0 if self.per_head else g
+                    assert np.array_equal(storage_to_values(kk, wl.dtype).astype(np.float64), st.Kd[vec][:, col]), \
+                        f"step {t} seq {s} head {g}: K rows differ from the oracle's pool"
+                    assert np.array_equal(storage_to_values(vv, wl.dtype).astype(np.float64), st.Vd[vec][:, col]), \
+                        f"step {t} seq {s} head {g}: V rows differ from the oracle's pool"
+            if self.per_head:
+                mkv.mkv_set_score_view(self.ctx, 0)

@@ -1,0 +1,149 @@
+"""GPU parity of deferred compaction: at the paper's cadence (trigger = budget) on the matrix-core
+kernels a step's eviction only marks the token's slot; the attention kernel masks marked slots,
+the finishing kernel skips them, and the rows are compacted when the spare slots are used up or a
+reader looks.  The results must be those of immediate compaction, i.e. the oracle's: the selection
+is checked on the device's own float32 score bits (read slot by slot, without compacting), the
+compacted pool against the oracle's pool bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import momentkv_oracle as O
+from paper_2605_29873_amd import inputs as X
+from tests.harness import DeferredRun, FreeRun, Progress, make_ctx, to_device
+
+pytestmark = pytest.mark.gpu
+
+WL = X.workloads()
+
+
+def _wl(G, Hkv, budget, W, alpha=0.8, M=(60, 260), batch=3, **kw):
+    base = dict(batch=batch, n_layers=1, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=128, dtype="bf16",
+                prefill_min=M[0], prefill_max=M[1], decode_budget=budget, evict_trigger=budget,
+                recent_window=W, alpha=alpha, steps=0, hh_prob=0.02, dip_period=32, dip_len=4)
+    base.update(kw)
+    return X.Workload("deferred", **base)
+
+
+@pytest.mark.parametrize("G,Hkv,budget,W,per_head,capacity,read_every", [
+    (4, 2, 300, 24, False, 0, 1000),      # default room (37 slots): compactions come from the room running out
+    (4, 2, 300, 0, False, 0, 7),          # the paper's W = 0; a reader every 7 steps
+    (7, 2, 600, 32, False, 0, 29),        # Qwen grouping, three slot blocks, 64 spare slots
+    (4, 2, 300, 24, True, 0, 13),         # one score vector, bitmap and retained set per KV head
+    (12, 4, 130, 10, False, 0, 11),       # 48 heads: the general finishing kernel
+    (4, 2, 64, 8, False, 64 + 1 + 3, 1000),   # three spare slots only: a compaction every third step
+    (2, 1, 40, 5, False, 40 + 1 + 100, 1000), # more spare slots than live tokens
+])
+def test_deferred_compaction_free_run_under_the_oracle(mkv, G, Hkv, budget, W, per_head, capacity, read_every):
+    wl = _wl(G, Hkv, budget, W)
+    dr = DeferredRun(mkv, wl, seqs=[0, 2], active=[0, 2], per_head=per_head, decode_capacity=capacity)
+    try:
+        dr.prefill()
+        steps = budget + 150
+        for t in range(steps):
+            dr.step(t, read=(t % read_every == read_every - 1 or t == steps - 1), check_abar=(t % 5 == 0))
+        assert dr.evictions == 2 * 150
+        assert dr.max_holes >= (2 if capacity else 5), "holes never accumulated: the case does not exercise the deferral"
+    finally:
+        dr.close()
+    print(f"deferred G={G} B_d={budget} W={W} per_head={per_head}: {dr.evictions} evictions, {dr.near_ties} near-ties, "
+          f"up to {dr.max_holes} holes in {dr.cap_seen} slots, evicted slots {min(dr.evicted_slots)}..{max(dr.evicted_slots)}, "
+          f"max |out err| {dr.max_out_err:.2e}, max score rel {dr.max_score_rel:.2e}")
+
+
+def test_deferred_compaction_with_the_static_scratch_entry_point(mkv):
+    wl = _wl(4, 2, 100, 8)
+    dr = DeferredRun(mkv, wl, static_scratch=True)
+    try:
+        dr.prefill()
+        for t in range(200):
+            dr.step(t, read=(t % 41 == 40 or t == 199))
+        assert dr.evictions == 3 * 100 and dr.max_holes >= 6
+    finally:
+        dr.close()
+
+
+def test_pool_loaded_above_the_budget_goes_through_the_general_selection(mkv):
+    # mkv_load_decode may leave more than budget + 1 tokens after the next append: the step then
+    # evicts several at once (general selection on a pool without holes), after which the cadence
+    # and the deferral resume
+    wl = _wl(4, 2, 100, 8, batch=2)
+    dr = DeferredRun(mkv, wl)
+    try:
+        dr.prefill()
+        for t in range(130):                                   # reach the cadence, leave holes behind
+            dr.step(t)
+        assert dr.max_holes >= 6
+        for s in range(wl.batch):
+            k, v, sc, pos = X.decode_snapshot(wl, 0, s, 104, 1000)
+            dk, dv = to_device(k, wl.dtype), to_device(v, wl.dtype)
+            mkv.mkv_load_decode(dr.ctx, 0, s, dk.data_ptr(), dv.data_ptr(), sc, pos, 1000)
+            st = dr.oracles[s]
+            st.load_decode(k, v, sc, pos, 1000)
+        # one step by hand: 105 live tokens -> 5 leave together
+        q, k, v = X.step_batch(wl, 0, 1000)
+        dq, dk, dv = (to_device(a, wl.dtype) for a in (q, k, v))
+        twin = make_ctx(mkv, wl, manual_evict=True, decode_capacity=120)      # for the pre-eviction score bits
+        for s in range(wl.batch):
+            kp, vp = X.prefill_kv(wl, 0, s)
+            a, b = to_device(kp, wl.dtype), to_device(vp, wl.dtype)
+            mkv.mkv_prefill_append(twin, 0, s, a.data_ptr(), b.data_ptr(), kp.shape[0])
+            ks, vs, sc, pos = X.decode_snapshot(wl, 0, s, 104, 1000)
+            a, b = to_device(ks, wl.dtype), to_device(vs, wl.dtype)
+            mkv.mkv_load_decode(twin, 0, s, a.data_ptr(), b.data_ptr(), sc, pos, 1000)
+        out = torch.zeros_like(dr.out)
+        mkv.mkv_decode_step(dr.ctx, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), dr.out.data_ptr())
+        mkv.mkv_decode_step(twin, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr())
+        torch.cuda.synchronize()
+        assert torch.allclose(out.float(), dr.out.float(), rtol=0, atol=4e-3)
+        for s in range(wl.batch):
+            st = dr.oracles[s]
+            st.decode_step(q[s], k[s], v[s], auto_evict=False)
+            S, P = mkv.mkv_read_scores(twin, 0, s)
+            E = O.select_evict(S, P, 5, wl.recent_window)
+            st.remove(0, E)
+            gs, gp = mkv.mkv_read_scores(dr.ctx, 0, s)
+            keep = O.survivors(105, E)
+            assert np.array_equal(gp, P[keep]) and np.array_equal(gs.view(np.uint32), S[keep].view(np.uint32))
+        mkv.mkv_destroy(twin)
+        for t in range(1001, 1060):                            # and on with the cadence
+            dr.step(t, read=(t == 1059))
+    finally:
+        dr.close()
+
+
+def test_explicit_minimal_capacity_keeps_compaction_immediate(mkv):
+    # decode_capacity = budget + 1 leaves no spare slot: every eviction shifts the rows at once
+    # (the one-row shift after the finishing kernel's selection), and no slot is ever marked
+    wl = _wl(4, 2, 50, 4, batch=1)
+    fr = FreeRun(mkv, wl, auto_capacity=51)
+    try:
+        fr.prefill()
+        for t in range(90):
+            fr.step(t, check_rows=(t % 9 == 0))
+            S, P, live, pend = mkv.mkv_read_slots(fr.auto, 0, 0, 64)
+            assert live.all() and pend == -1 and S.size == min(t + 1, 50)
+        assert fr.evictions == 40
+    finally:
+        fr.close()
+
+
+@pytest.mark.slow
+def test_cfg4_qwen_layer_deferred_compaction_from_an_empty_pool(mkv, capsys):
+    """The Qwen-shaped layer at full size in the configuration the bench times (default capacity:
+    64 spare slots), all 8 sequences active, 1500 steps from an empty pool; sequences 2 and 7 are
+    followed, the readers look every 200 steps."""
+    wl = WL["cfg4"]
+    dr = DeferredRun(mkv, wl, seqs=[2, 7], active=range(wl.batch))
+    alive = Progress(capsys, "cfg4 deferred")
+    try:
+        dr.prefill()
+        for t in range(1500):
+            dr.step(t, read=(t % 200 == 199 or t == 1499), check_abar=(t % 50 == 0))
+            alive.tick(f"step {t} of 1500, {dr.evictions} evictions")
+        assert dr.evictions == 2 * (1500 - 512) and dr.max_holes >= 60
+    finally:
+        dr.close()
+    spread = np.percentile(dr.evicted_slots, [0, 25, 50, 75, 100]).astype(int).tolist()
+    print(f"cfg4 deferred: {dr.evictions} evictions, {dr.near_ties} near-ties, up to {dr.max_holes} holes, "
+          f"evicted-slot quartiles {spread}, max |out err| {dr.max_out_err:.2e}, max score rel {dr.max_score_rel:.2e}")
