@@ -98,3 +98,43 @@ def test_header_is_plain_c_and_the_binding_mirrors_its_struct(tmp_path):
     assert int(out[0]) == C.sizeof(B.mkv_config)
     for f, off in zip(fields, out[1:]):
         assert int(off) == getattr(B.mkv_config, f).offset, f
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """The host side of the ABI (configuration checks, layout arithmetic, argument handling in
+    csrc/mkv_api.hip) built with AddressSanitizer and UBSan on the host pass only, driven by
+    tests/abi_host_driver.c.  No GPU code is sanitized and no GPU is needed."""
+    import subprocess
+    from paper_2605_29873_amd import build as Bd
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host", "-fno-omit-frame-pointer"]
+    csrc = os.path.join(ROOT, "paper_2605_29873_amd", "csrc")
+    objs = []
+    for src in Bd.SOURCES:                      # only the API file holds host logic; the others bring the launch stubs
+        obj = tmp_path / src.replace(".hip", ".o")
+        plain = os.path.join(ROOT, "paper_2605_29873_amd", "_build", src.replace(".hip", ".o"))
+        if src != "mkv_api.hip" and os.path.exists(plain):
+            objs.append(plain)
+            continue
+        flags = san if src == "mkv_api.hip" else []
+        subprocess.run([hipcc, *Bd.FLAGS, *flags, "-I", os.path.join(ROOT, "include"), "-c",
+                        os.path.join(csrc, src), "-o", str(obj)], check=True, capture_output=True)
+        objs.append(str(obj))
+    lib = tmp_path / "libmkv_san.so"
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", str(lib),
+                    "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan"], check=True, capture_output=True)
+    exe = tmp_path / "abi_host_driver"
+    clang = "/opt/rocm/llvm/bin/clang"
+    subprocess.run([clang, "-std=c99", "-Wall", "-Werror", "-g", "-fsanitize=address", "-fsanitize=undefined",
+                    "-fno-sanitize-recover=undefined", "-shared-libsan", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "abi_host_driver.c"), "-o", str(exe),
+                    f"-L{tmp_path}", "-lmkv_san", f"-Wl,-rpath,{tmp_path}"], check=True, capture_output=True)
+    rt_dir = os.path.dirname(subprocess.run([clang, "--print-file-name=libclang_rt.asan-x86_64.so"],
+                                            check=True, capture_output=True, text=True).stdout.strip())
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1",
+               LD_LIBRARY_PATH=rt_dir + ":/opt/rocm/lib:" + os.environ.get("LD_LIBRARY_PATH", ""))
+    run = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=120)
+    assert run.returncode == 0, run.stdout[-2000:] + run.stderr[-4000:]
+    assert run.stdout.strip().endswith("ok")
+    assert "runtime error" not in run.stderr and "AddressSanitizer" not in run.stderr
