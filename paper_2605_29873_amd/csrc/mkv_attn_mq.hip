@@ -17,6 +17,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <type_traits>
+
 namespace mkv {
 namespace {
 
@@ -305,8 +307,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     };
     // the 32 bitmap bits of a tile of pool keys (bit i: key i of the tile is an evicted slot); the
     // load is unconditional like the others (word 0 for tiles that need none)
-    auto load_dead = [&](int tt, int t_end) __attribute__((always_inline)) {
-      if constexpr (!LAZY) return 0u;
+    auto load_dead = [&](int tt, int t_end, auto masked) __attribute__((always_inline)) {
+      if constexpr (!LAZY || !decltype(masked)::value) return 0u;
       else {
         const int seg = tile_seg(tt);
         const int jb = tile_key(tt, seg);
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     constexpr float kSlack = 8.0f;
     // scores of one tile against the rows of each block: x[nb][4h + i] = logit of key 16h + 4j + i (base 2), -inf
     // where masked; decode logits are staged for the score update
-    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], uint32_t dmask, float (&x)[NB][8]) __attribute__((always_inline)) {
+    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], uint32_t dmask, auto masked, float (&x)[NB][8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
       const int jn = pick3(seg, p1, dp, d1);
@@ -366,7 +368,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
             const int key = key0 + i;
             // past the segment, or an appended token that comes after this row's own (causal order)
             bool ok = key < jn && !(seg == 2 && key - n0 > qi[nb]);
-            if constexpr (LAZY)      // an evicted slot that still holds its rows
+            if constexpr (LAZY && decltype(masked)::value)      // an evicted slot that still holds its rows
               ok = ok && !(seg == 1 && (((dmask >> (16 * h + 4 * j4 + i)) & 1u) || key == pend_slot));
             x[nb][4 * h + i] = ok ? sx[i] : -INFINITY;
           }
@@ -435,16 +437,18 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // registers: as soon as the scores of a tile are formed its K registers take the next tile's
     // K, and as soon as the values are accumulated its V registers take the next tile's V, so a
     // wave always has loads in flight.
-    auto run_tiles = [&](int t_lo, int t_hi) __attribute__((always_inline)) {
+    // `masked`: the piece holds keys of the decode pool, whose slots may be marked (LAZY only); a
+    // piece of prompt keys alone runs the plain loop
+    auto run_tiles = [&](int t_lo, int t_hi, auto masked) __attribute__((always_inline)) {
       uint4 kbuf[2][4], vbuf[2][4];
       int tt = t_lo + wave;
-      uint32_t dmask = load_dead(tt, t_hi);
+      uint32_t dmask = load_dead(tt, t_hi, masked);
       load_k(tt, t_hi, kbuf);
       load_v(tt, t_hi, vbuf);
       while (tt < t_hi) {
         float x[NB][8];
-        score_tile(tt, kbuf, dmask, x);
-        dmask = load_dead(tt + WPB, t_hi);
+        score_tile(tt, kbuf, dmask, masked, x);
+        dmask = load_dead(tt + WPB, t_hi, masked);
         load_k(tt + WPB, t_hi, kbuf);
         PairB pb[NB];
 #pragma unroll
@@ -460,7 +464,8 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // by the whole work-group
     for (int t_lo = 0; t_lo < ntile; ++win) {
       const int t_hi = min(ntile, ntp + (win + 1) * WT);
-      run_tiles(t_lo, t_hi);
+      if (LAZY && ntd > 0) run_tiles(t_lo, t_hi, std::true_type{});
+      else run_tiles(t_lo, t_hi, std::false_type{});
       const int wk0 = win * SK;
       const int nk = min(dp - d0 - wk0, SK);
       const bool last = t_hi == ntile;
@@ -666,9 +671,12 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   float ipre[kPreS];
   // deferred compaction: the word of each vector's slot bitmap that holds this slot's bit
   uint32_t dpre[kPreS];
+  int hpre[kPreS];                       // and the vector's hole count (decides whether this step selects)
 #pragma unroll
-  for (int sv = 0; sv < kPreS; ++sv)
+  for (int sv = 0; sv < kPreS; ++sv) {
     dpre[sv] = (s.lazy && sv < s.S && j < n1) ? a.lv.dead[((size_t)b * s.S + sv) * s.capw + (j >> 5)] : 0u;
+    hpre[sv] = (s.lazy && sv < s.S) ? a.lv.nholes[b * s.S + sv] : 0;
+  }
   if (j < n1) {
     if constexpr (ONE) {
       const float* lg0 = a.sc.logits + logit_index(s, b, rows, 0, j);
@@ -745,7 +753,15 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     unsigned long long key = ~0ull;
     const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
     const int vec = b * s.S + sv;
-    const bool pick_one = one_out && n1 - (s.lazy ? a.lv.nholes[vec] : 0) == s.budget + 1;
+    int holes = 0;
+    if (sv < kPreS) {
+      holes = hpre[0];
+#pragma unroll
+      for (int u = 1; u < kPreS; ++u) holes = (sv == u) ? hpre[u] : holes;
+    } else if (s.lazy) {
+      holes = a.lv.nholes[vec];
+    }
+    const bool pick_one = one_out && n1 - holes == s.budget + 1;
     unsigned long long* key_dst = s.lazy ? a.lv.pend + (size_t)(n1 & 1) * s.B * s.S + vec : a.sc.evict_key + vec;
     float I = 0.f;                       // previous score of the slot (0 for one appended now, Eq. 6)
     uint32_t dword = 0u;
