@@ -585,7 +585,9 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
 //
 // ONE: a single query row and at most 32 heads (the plain decode step of the usual layers), where a
 // slot's logits fit in registers and are fetched before the normalisers are rebuilt.
-template <bool ONE>
+// LAZY: deferred compaction (Shape::lazy); a separate instantiation so that the ordinary one
+// carries none of its loads and tests.
+template <bool ONE, bool LAZY>
 __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishMqArgs a) {
   const Shape& s = a.s;
   const int b = blockIdx.y;
@@ -669,13 +671,14 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   float xpre[kPre];
   constexpr int kPreS = 8;               // score vectors whose previous value is fetched up front too
   float ipre[kPreS];
-  // deferred compaction: the word of each vector's slot bitmap that holds this slot's bit
-  uint32_t dpre[kPreS];
-  int hpre[kPreS];                       // and the vector's hole count (decides whether this step selects)
-#pragma unroll
-  for (int sv = 0; sv < kPreS; ++sv) {
-    dpre[sv] = (s.lazy && sv < s.S && j < n1) ? a.lv.dead[((size_t)b * s.S + sv) * s.capw + (j >> 5)] : 0u;
-    hpre[sv] = (s.lazy && sv < s.S) ? a.lv.nholes[b * s.S + sv] : 0;
+  // deferred compaction: the word of the vector's slot bitmap that holds this slot's bit
+  // and its hole count, which decides whether this step selects (first vector up front, the
+  // usual single one; further vectors fetch theirs when their turn comes)
+  [[maybe_unused]] uint32_t dpre0 = 0u;
+  [[maybe_unused]] int hpre0 = 0;
+  if constexpr (LAZY) {
+    if (j < n1) dpre0 = a.lv.dead[(size_t)b * s.S * s.capw + (j >> 5)];
+    hpre0 = a.lv.nholes[b * s.S];
   }
   if (j < n1) {
     if constexpr (ONE) {
@@ -754,30 +757,27 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     const size_t si = ((size_t)b * s.S + sv) * s.cap + j;
     const int vec = b * s.S + sv;
     int holes = 0;
-    if (sv < kPreS) {
-      holes = hpre[0];
-#pragma unroll
-      for (int u = 1; u < kPreS; ++u) holes = (sv == u) ? hpre[u] : holes;
-    } else if (s.lazy) {
-      holes = a.lv.nholes[vec];
+    uint32_t dword = 0u;
+    if constexpr (LAZY) {
+      if (sv == 0) {
+        holes = hpre0;
+        dword = dpre0;
+      } else {
+        holes = a.lv.nholes[vec];
+        if (j < n1) dword = a.lv.dead[(size_t)vec * s.capw + (j >> 5)];
+      }
     }
     const bool pick_one = one_out && n1 - holes == s.budget + 1;
-    unsigned long long* key_dst = s.lazy ? a.lv.pend + (size_t)(n1 & 1) * s.B * s.S + vec : a.sc.evict_key + vec;
+    unsigned long long* key_dst = LAZY ? a.lv.pend + (size_t)(n1 & 1) * s.B * s.S + vec : a.sc.evict_key + vec;
     float I = 0.f;                       // previous score of the slot (0 for one appended now, Eq. 6)
-    uint32_t dword = 0u;
     if (sv < kPreS) {
       I = ipre[0];
-      dword = dpre[0];
 #pragma unroll
-      for (int u = 1; u < kPreS; ++u) {
-        I = (sv == u) ? ipre[u] : I;
-        dword = (sv == u) ? dpre[u] : dword;
-      }
-    } else if (j < n1) {
-      if (j < n0) I = a.lv.score[si];
-      if (s.lazy) dword = a.lv.dead[(size_t)vec * s.capw + (j >> 5)];
+      for (int u = 1; u < kPreS; ++u) I = (sv == u) ? ipre[u] : I;
+    } else if (j < n0) {
+      I = a.lv.score[si];
     }
-    const bool alive = !((dword >> (j & 31)) & 1u);   // an evicted slot takes no update and is no candidate
+    const bool alive = !LAZY || !((dword >> (j & 31)) & 1u);   // an evicted slot takes no update and is no candidate
     if constexpr (ONE) {
       if (j < n1) {
         float sum0 = 0.f, sum1 = 0.f;
@@ -921,7 +921,8 @@ hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& 
   const int slots = one ? kFinishThreads : kSlotsMulti;
   dim3 grid((rows + kRowsPerBlock - 1) / kRowsPerBlock + (max_nd_eff + slots - 1) / slots, s.B);
   const size_t smem = (size_t)(rows + 2 * kFinishThreads) * sizeof(float);   // slot blocks: normalisers + exchange
-  auto kern = one ? finish_mq_kernel<true> : finish_mq_kernel<false>;
+  auto kern = one ? (s.lazy ? finish_mq_kernel<true, true> : finish_mq_kernel<true, false>)
+                  : (s.lazy ? finish_mq_kernel<false, true> : finish_mq_kernel<false, false>);
   if (tm) hipExtLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, grid, dim3(kFinishThreads), smem, st, a);
   return hipGetLastError();
