@@ -578,7 +578,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   if (e != hipSuccess) return poison(c, e, "attention launch");
-  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
+  if (mq) e = launch_finish_mq(c->shape, lv, sc, q_len, out, mask, lens, max_n1, (int)R, total_keys < (1ll << 31), c->stream, pe ? &t_fin : nullptr);
   else e = launch_finish(c->shape, lv, sc, out, mask, max_n1, (int)R, c->stream, pe ? &t_fin : nullptr);
   if (e != hipSuccess) return poison(c, e, "finish launch");
   for (int b = 0; b < B; ++b) {

@@ -552,6 +552,7 @@ struct FinishMqArgs {
   float inv_H;
   int R, Q, HP, passes;
   int RPS;      // rows per partial slot: 16 x row blocks of the attention pass
+  int narrow;   // the flattened key axis of the launch fits 31 bits: slot arithmetic in 32-bit divisions
 };
 
 constexpr int kFinishThreads = 256;
@@ -567,7 +568,14 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   const int pass = hl / a.HP;
   const int ul = g * a.passes + pass;
   const long long off_u = off_b + (long long)ul * (L + s.piece_pad) + s.piece_pad;   // the unit's first key on the flattened axis
-  const long long kf = off_u / a.R, kl = (off_u + L - 1) / a.R;
+  long long kf, kl;
+  if (a.narrow) {       // (a 64-bit division is a long subroutine, and the loads below wait for it)
+    kf = (uint32_t)off_u / (uint32_t)a.R;
+    kl = (uint32_t)(off_u + L - 1) / (uint32_t)a.R;
+  } else {
+    kf = off_u / a.R;
+    kl = (off_u + L - 1) / a.R;
+  }
   RowSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * a.passes + ul;
   p.ns = (int)(kl - kf) + 1;
@@ -690,10 +698,43 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     for (int sv = 0; sv < kPreS; ++sv)
       ipre[sv] = (sv < s.S && j < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + j] : 0.f;
   }
-  // normalisers of all rows, `parts` threads per row, each folding its share of the row's pieces
+  // ONE: every wave rebuilds the (at most 32) normalisers by itself, in registers: lane l takes
+  // row l % 32 and the pieces of parity l / 32, the two halves meet through one lane exchange, and
+  // the sums below read row h's value from lane h -- no LDS, no barrier.
+  [[maybe_unused]] float lse_lane = 0.f;
+  if constexpr (ONE) {
+    const int x = lane & 31, half = lane >> 5;
+    float m_loc = -INFINITY, l_loc = 0.f;
+    if (x < rows) {
+      const RowSpan sp = row_span(a, off_b, b, x, 0, Lb);
+      const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * a.RPS + sp.row);
+      for (int i0 = half; i0 < sp.ns; i0 += 16) {    // eight loads in flight
+        float2 v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = ml[(size_t)min(i0 + 2 * k, sp.ns - 1) * a.RPS];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          if (i0 + 2 * k >= sp.ns) continue;
+          if (v[k].x > m_loc) {            // a piece without visible keys has reference -inf, sum 0
+            l_loc = fmaf(l_loc, fast_exp2(m_loc - v[k].x), v[k].y);
+            m_loc = v[k].x;
+          } else if (v[k].x != -INFINITY) {
+            l_loc = fmaf(v[k].y, fast_exp2(v[k].x - m_loc), l_loc);
+          }
+        }
+      }
+    }
+    const float m_o = __shfl_xor(m_loc, 32), l_o = __shfl_xor(l_loc, 32);
+    const float mx = fmaxf(m_loc, m_o);
+    float L = 0.f;
+    if (m_loc != -INFINITY) L = l_loc * fast_exp2(m_loc - mx);
+    if (m_o != -INFINITY) L = fmaf(l_o, fast_exp2(m_o - mx), L);
+    lse_lane = mx + log2f(L);
+  }
+  // otherwise: normalisers of all rows, `parts` threads per row, each folding its share of the row's pieces
   // into a running (reference, sum) pair from one round of loads; smem: [rows], then two arrays
   // [parts][rc] through which the parts of a row meet
-  {
+  if constexpr (!ONE) {
     const int rc = min(rows, kFinishThreads);
     const int parts = kFinishThreads / rc;
     float* red_m = smem + rows;
@@ -783,8 +824,10 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
         float sum0 = 0.f, sum1 = 0.f;
 #pragma unroll
         for (int h = 0; h < kPre; h += 2) {
-          if (h >= sv * Hs && h < (sv + 1) * Hs) sum0 += fast_exp2(xpre[h] - smem[h]);
-          if (h + 1 >= sv * Hs && h + 1 < (sv + 1) * Hs) sum1 += fast_exp2(xpre[h + 1] - smem[h + 1]);
+          const float n0h = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lse_lane), h));
+          const float n1h = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, lse_lane), h + 1));
+          if (h >= sv * Hs && h < (sv + 1) * Hs) sum0 += fast_exp2(xpre[h] - n0h);
+          if (h + 1 >= sv * Hs && h + 1 < (sv + 1) * Hs) sum1 += fast_exp2(xpre[h + 1] - n1h);
         }
         const float abar = alive ? (sum0 + sum1) * inv_Hs : 0.f;
         I = fmaf(s.alpha, I, abar);
@@ -909,13 +952,14 @@ hipError_t attn_mq_groups_per_cu(const Shape& s, int* out) {
 
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
-                            hipStream_t st, const KernelTimer* tm) {
+                            bool narrow, hipStream_t st, const KernelTimer* tm) {
   FinishMqArgs a;
   a.s = s; a.lv = lv; a.sc = sc; a.out = out; a.mask = mask; a.lens = lens; a.inv_H = 1.0f / (float)s.H;
   a.R = keys_per_group; a.Q = q_len;
   a.HP = mq_heads_per_pass(s.G, q_len);
   a.passes = (s.G + a.HP - 1) / a.HP;
   a.RPS = 16 * mq_row_blocks(s.G, q_len);
+  a.narrow = narrow ? 1 : 0;
   const int rows = s.H * q_len;
   const bool one = q_len == 1 && s.H <= 32;
   const int slots = one ? kFinishThreads : kSlotsMulti;

@@ -118,9 +118,10 @@ hipError_t launch_attn_mq(const Shape& s, const LayerView& lv, const Scratch& sc
                           const void* k_new, const void* v_new, const SeqMask& mask, const InlineLens& lens,
                           int keys_per_group, int n_groups, hipStream_t st, const KernelTimer* tm = nullptr);
 hipError_t attn_mq_groups_per_cu(const Shape& s, int* out);
+// `narrow`: the launch's flattened key axis is shorter than 2^31 positions.
 hipError_t launch_finish_mq(const Shape& s, const LayerView& lv, const Scratch& sc, int q_len, void* out,
                             const SeqMask& mask, const InlineLens& lens, int max_nd_eff, int keys_per_group,
-                            hipStream_t st, const KernelTimer* tm = nullptr);
+                            bool narrow, hipStream_t st, const KernelTimer* tm = nullptr);
 
 // Compaction of the slots marked in LayerView::dead (plus the pending selection) for the masked
 // sequences: survivors move down in order, the bitmaps are cleared, nd becomes the live count.
