@@ -625,9 +625,11 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     const float* ml = a.sc.part_ml + (sp.slot0 * a.RPS + sp.row) * 2;
     const float2* po = reinterpret_cast<const float2*>(a.sc.part_o + (sp.slot0 * a.RPS + sp.row) * kD) + lane;
     const size_t ostride = (size_t)a.RPS * kD / 2;
-    // a row rarely has more than a few pieces: their partial outputs are fetched alongside the
-    // (reference, sum) pairs rather than after the weights are known
-    constexpr int kPrePieces = 4;
+    // the first pieces' partial outputs are fetched alongside the (reference, sum) pairs rather
+    // than after the weights are known: sixteen covers every row of a batch that fills the chip,
+    // and half the pieces of a single sequence spread over all work-groups (with four up front and
+    // eight per further round the batch-1 Llama layer took 16.2 us per step, now 15.8)
+    constexpr int kPrePieces = 16;
     float2 pre[kPrePieces];
 #pragma unroll
     for (int i = 0; i < kPrePieces; ++i) pre[i] = i < ns ? po[(size_t)i * ostride] : make_float2(0.f, 0.f);
@@ -639,18 +641,18 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
       const float w = fast_exp2(__shfl(m_first, i) - mx);     // 0 for a piece without visible keys
       if (i < ns) { o.x = fmaf(w, pre[i].x, o.x); o.y = fmaf(w, pre[i].y, o.y); }
     }
-    // further pieces (few sequences spread over many work-groups), eight loads at a time
-    for (int i0 = kPrePieces; i0 < ns; i0 += 8) {
-      float2 v[8];
-      float w[8];
+    // further pieces (few sequences spread over many work-groups), sixteen loads at a time
+    for (int i0 = kPrePieces; i0 < ns; i0 += 16) {
+      float2 v[16];
+      float w[16];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 16; ++k) {
         const int i = min(i0 + k, ns - 1);
         v[k] = po[(size_t)i * ostride];
         w[k] = ml[(size_t)i * mlstride];
       }
 #pragma unroll
-      for (int k = 0; k < 8; ++k) {
+      for (int k = 0; k < 16; ++k) {
         const float e = i0 + k < ns ? fast_exp2(w[k] - mx) : 0.f;
         o.x = fmaf(e, v[k].x, o.x); o.y = fmaf(e, v[k].y, o.y);
       }
@@ -708,8 +710,8 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     if (x < rows) {
       const RowSpan sp = row_span(a, off_b, b, x, 0, Lb);
       const float2* ml = reinterpret_cast<const float2*>(a.sc.part_ml) + (sp.slot0 * a.RPS + sp.row);
-      for (int i0 = half; i0 < sp.ns; i0 += 16) {    // eight loads in flight
-        float2 v[8];
+      for (int i0 = half; i0 < sp.ns; i0 += 16) {    // eight loads in flight (sixteen: 0.3 us faster with 32
+        float2 v[8];                                 // pieces per row, 0.3 us slower with the usual two or three)
 #pragma unroll
         for (int k = 0; k < 8; ++k) v[k] = ml[(size_t)min(i0 + 2 * k, sp.ns - 1) * a.RPS];
 #pragma unroll
