@@ -593,16 +593,24 @@ class DeferredRun:
             if s in self.oracles:
                 self.oracles[s].load_decode(k, v, sc, pos, t_now)
 
-    def step(self, t: int, read: bool = False, check_abar: bool = False):
+    def step(self, t: int, read: bool = False, check_abar: bool = False, active=None):
+        """active: the sequences that take this step (default: all of self.active); the others
+        pause -- nothing of theirs may change, marked slots and pending selection included."""
         wl, mkv = self.wl, self.mkv
         q, k, v = X.step_batch(wl, 0, t)
         dq, dk, dv = (to_device(a, wl.dtype) for a in (q, k, v))
-        self.step_fn(self.ctx, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), self.out.data_ptr(), self.mask)
+        mask = self.mask
+        if active is not None:
+            mask = np.zeros(wl.batch, dtype=np.uint8)
+            mask[list(active)] = 1
+        self.step_fn(self.ctx, 0, dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), self.out.data_ptr(), mask)
         torch.cuda.synchronize()
         got = from_device(self.out)
         rtol, atol = OUT_TOL[wl.dtype]
         cap = 16384
         for s in self.seqs:
+            if not mask[s]:
+                continue
             st = self.oracles[s]
             ref, abar = st.decode_step(q[s], k[s], v[s], auto_evict=False)
             err = np.abs(got[s] - ref)

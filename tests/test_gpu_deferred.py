@@ -128,6 +128,95 @@ def test_explicit_minimal_capacity_keeps_compaction_immediate(mkv):
         fr.close()
 
 
+def test_sequences_that_pause_keep_their_marked_slots_and_pending_selection(mkv):
+    # sequence 1 takes every third step only, sequence 2 stops for 40 steps in the middle: a paused
+    # sequence's bitmap, hole count and pending selection must wait for it unchanged
+    wl = _wl(4, 2, 48, 6, batch=3)
+    dr = DeferredRun(mkv, wl)
+    try:
+        dr.prefill()
+        for t in range(260):
+            act = [0] + ([1] if t % 3 == 0 else []) + ([2] if not 100 <= t < 140 else [])
+            dr.step(t, read=(t % 37 == 36), active=act, check_abar=(t % 7 == 0))
+        dr.step(260, read=True)
+        assert dr.evictions == (261 - 48) + (87 + 1 - 48) + (221 - 48) and dr.max_holes >= 5
+    finally:
+        dr.close()
+
+
+def test_manual_calls_on_a_context_with_marked_slots(mkv):
+    # mkv_evict (nothing to evict: it only compacts), mkv_write_scores (compacts, then overwrites the
+    # scores both sides go on with) and a change of the score view in between the steps
+    wl = _wl(4, 2, 40, 4, batch=2)
+    dr = DeferredRun(mkv, wl)
+    rng = np.random.default_rng(11)
+    try:
+        dr.prefill()
+        for t in range(150):
+            dr.step(t, read=(t % 50 == 49))
+            if t in (60, 61, 97):
+                mkv.mkv_evict(dr.ctx, 0, -1)
+                for s in range(wl.batch):
+                    S, P, live, pend = mkv.mkv_read_slots(dr.ctx, 0, s, 256)
+                    assert live.all() and pend == -1 and S.size == 40
+            if t in (75, 120):
+                for s in range(wl.batch):
+                    inject = (rng.random(40, dtype=np.float32) * 0.01).astype(np.float32)
+                    mkv.mkv_write_scores(dr.ctx, 0, s, inject)
+                    dr.oracles[s].I[0] = inject.astype(np.float64)
+        assert dr.evictions == 2 * 110
+    finally:
+        dr.close()
+
+
+def test_rows_from_the_producer_on_a_context_with_deferred_compaction(mkv):
+    """mkv_project_append writes the next token's row into the first free slot at the end of the
+    pool; with deferred compaction that slot may first have to be made (a compaction when the spare
+    slots are used up).  Same producer, same steps on a context that compacts at once: the retained
+    tokens must agree and the scores be equal up to the rounding of a different summation order."""
+    wl = _wl(4, 2, 40, 4, batch=2, M=(30, 50))
+    hidden, theta = 512, 500000.0
+    lazy = make_ctx(mkv, wl, manual_evict=False, decode_capacity=0)
+    eager = make_ctx(mkv, wl, manual_evict=False, decode_capacity=41)
+    try:
+        for s in range(wl.batch):
+            k, v = X.prefill_kv(wl, 0, s)
+            dk, dv = to_device(k, "bf16"), to_device(v, "bf16")
+            for c in (lazy, eager):
+                mkv.mkv_prefill_append(c, 0, s, dk.data_ptr(), dv.data_ptr(), k.shape[0])
+        wk, wv = X.projection_weights(wl, 0, hidden)
+        dwk, dwv = to_device(wk, "bf16"), to_device(wv, "bf16")
+        out_l = torch.zeros((wl.batch, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda")
+        out_e = torch.zeros_like(out_l)
+        seen_holes = 0
+        for t in range(120):
+            x = X.step_hidden(wl, 0, t, hidden)
+            q, _, _ = X.step_batch(wl, 0, t)
+            dx, dq = to_device(x, "bf16"), to_device(q, "bf16")
+            dpos = torch.full((wl.batch,), 1000 + t, dtype=torch.int32, device="cuda")
+            for c, o in ((lazy, out_l), (eager, out_e)):
+                mkv.mkv_project_append(c, 0, dx.data_ptr(), dwk.data_ptr(), dwv.data_ptr(), hidden, dpos.data_ptr(), theta)
+                mkv.mkv_decode_step(c, 0, dq.data_ptr(), None, None, o.data_ptr())
+            torch.cuda.synchronize()
+            assert torch.allclose(out_l.float(), out_e.float(), rtol=2e-2, atol=2e-3)
+            S, P, live, pend = mkv.mkv_read_slots(lazy, 0, 0, 256)
+            seen_holes = max(seen_holes, int((~live).sum()))
+            if t % 23 == 22 or t == 119:
+                for s in range(wl.batch):
+                    sl, pl = mkv.mkv_read_scores(lazy, 0, s)
+                    se, pe = mkv.mkv_read_scores(eager, 0, s)
+                    assert np.array_equal(pl, pe), f"step {t} seq {s}: retained tokens differ"
+                    assert np.allclose(sl, se, rtol=1e-5, atol=1e-9)
+                    for g in range(wl.n_kv_heads):
+                        kl, vl = mkv.mkv_read_kv(lazy, 0, s, 0, g, 128, mkv.MKV_BF16)
+                        ke, ve = mkv.mkv_read_kv(eager, 0, s, 0, g, 128, mkv.MKV_BF16)
+                        assert np.array_equal(kl, ke) and np.array_equal(vl, ve)
+        assert seen_holes >= 5
+    finally:
+        mkv.mkv_destroy(lazy)
+        mkv.mkv_destroy(eager)
+
+
 @pytest.mark.slow
 def test_cfg4_qwen_layer_deferred_compaction_from_an_empty_pool(mkv, capsys):
     """The Qwen-shaped layer at full size in the configuration the bench times (default capacity:
