@@ -509,18 +509,44 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     c->prof.evicted[c->prof.used] = 0;
     t_attn = {pe[0], pe[1]}; t_fin = {pe[2], pe[3]}; t_ev = {pe[4], pe[5]};
   }
+  // work-groups of the attention launch for a flattened key axis of `total` positions
+  const int target = mq ? c->mq_target_groups : c->target_groups;
+  auto plan = [&](long long total, long long* R_out) -> long long {
+    long long R = c->cfg.split_keys ? c->cfg.split_keys : (total + target - 1) / target;
+    if (R < 64) R = 64;       // a work-group takes at least 64 positions (sizes the partial buffers)
+    const long long r_min = (total + c->lay.max_groups - 1) / c->lay.max_groups;
+    if (R < r_min) R = r_min;
+    *R_out = R;
+    return (total + R - 1) / R;
+  };
   char* static_base = nullptr;
   if (static_scratch) {
     hipError_t se = static_scratch_base(&static_base);
     if (se != hipSuccess) return fail_hip(c, se, "address of the static scratch array");
+    // does the step's scratch fit?  Decided here, before anything is enqueued, on the slots in use
+    // now: a compaction below can only shorten the key axis
+    long long total_now = 0, R_now = 0;
+    for (int b = 0; b < B; ++b)
+      if (mask.active(b)) {
+        const size_t i = (size_t)layer * B + b;
+        total_now += (long long)c->cfg.n_kv_heads * passes * (c->h_mlen[i] + c->h_nd[i] + q_len + P);
+      }
+    // (a shorter axis may split into a few more ranges, never more than the launch's target)
+    long long groups_most = plan(total_now, &R_now);
+    if (groups_most < target) groups_most = target;
+    const size_t slots = (size_t)groups_most + (size_t)B * c->cfg.n_kv_heads * passes;
+    Scratch probe;
+    const size_t need = carve_static(c, static_base, slots, mq ? 16 * mq_row_blocks(G, q_len) : c->lay.HL, q_len, &probe);
+    if (need > kStaticScratchBytes)
+      return fail(c, MKV_ERR_CAPACITY, fmt("this step needs %zu bytes of scratch, the static array holds %zu: use "
+                                           "mkv_decode_step", need, kStaticScratchBytes));
   }
   // 2. deferred compaction: a sequence whose slots are used up gets its holes closed first (the
   //    live tokens stay what they are; only their slots change)
   bool timed_evict = false;
   if (need_room) {
     Scratch fsc = scratch_view(c);
-    if (static_scratch && carve_static(c, static_base, 0, 1, q_len, &fsc) > kStaticScratchBytes)
-      return fail(c, MKV_ERR_CAPACITY, "the compaction's scratch does not fit the static array: use mkv_decode_step");
+    if (static_scratch) (void)carve_static(c, static_base, 0, 1, q_len, &fsc);   // fits: it is part of the step's
     bool fired = false;
     int frc = flush_holes(c, layer, mask, fsc, pe ? &t_ev : nullptr, &fired);
     if (frc != MKV_OK) return frc;
@@ -557,23 +583,17 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   // and a unit count that divides (or is divided by) the work-group count, every range then starts
   // and ends on unit boundaries and no work-group pays for two pieces (the 86 GB context, 256
   // units on 256 work-groups: 419 -> 406 us per layer); a range may start and end at any key.
-  const int target = mq ? c->mq_target_groups : c->target_groups;
-  long long R = c->cfg.split_keys ? c->cfg.split_keys : (total_keys + target - 1) / target;
-  if (R < 64) R = 64;       // a work-group takes at least 64 positions (sizes the partial buffers)
-  const long long r_min = (total_keys + c->lay.max_groups - 1) / c->lay.max_groups;
-  if (R < r_min) R = r_min;
+  long long R = 0;
+  const int n_groups = (int)plan(total_keys, &R);
   if (R > INT32_MAX - 63) return fail(c, MKV_ERR_CAPACITY, "key range per work-group overflows");
-  const int n_groups = (int)((total_keys + R - 1) / R);
   hipError_t e;
   Scratch sc = scratch_view(c);
   if (static_scratch) {
     // partial slots this launch can touch: one per work-group plus one per (sequence, KV head, pass)
     const size_t slots = (size_t)n_groups + (size_t)B * c->cfg.n_kv_heads * passes;
     const int rows = mq ? 16 * mq_row_blocks(G, q_len) : c->lay.HL;
-    const size_t need = carve_static(c, static_base, slots, rows, q_len, &sc);
-    if (need > kStaticScratchBytes)
-      return fail(c, MKV_ERR_CAPACITY, fmt("this step needs %zu bytes of scratch, the static array holds %zu: use "
-                                           "mkv_decode_step", need, kStaticScratchBytes));
+    if (carve_static(c, static_base, slots, rows, q_len, &sc) > kStaticScratchBytes)    // checked above
+      return fail(c, MKV_ERR_CAPACITY, "static scratch");
   }
   if (mq) e = launch_attn_mq(c->shape, lv, sc, q_len, q, k_new, v_new, mask, lens, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
   else e = launch_attn(c->shape, lv, sc, q, k_new, v_new, mask, (int)R, n_groups, c->stream, pe ? &t_attn : nullptr);
