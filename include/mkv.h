@@ -91,9 +91,10 @@ typedef struct {
   float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
   int32_t score_mode;      /* mkv_score_mode                                                     */
   int32_t split_keys;      /* tuning: length of the key range one attention work-group takes (multiple
-                              of 16, >= 64; every (sequence, KV head) unit counts 256 positions more
-                              than its keys, the cost of starting on it); 0 => chosen per step so
-                              that the launch just fills the chip                               */
+                              of 16, >= 64; every (sequence, KV head) unit counts 384 positions more
+                              than its keys: 256 in front for the cost of starting on it, 128 behind
+                              for the extra work at its end); 0 => chosen per step so that the launch
+                              just fills the chip                                               */
   int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default (the
                               matrix-core kernel for bf16 x 128 layers, else the vector-ALU
                               kernel); 1..15 force variants of the latter, 16.. of the former

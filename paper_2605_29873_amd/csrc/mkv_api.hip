@@ -56,6 +56,14 @@ constexpr int kMaxGroups = 4096;          // attention work-groups per launch, a
 // workload (batch-1 Llama layer 11.4 -> 9.0 us attention, Qwen-shaped layer 26.7 -> 25.0 us,
 // ragged Llama layer 63.9 -> 63.1 us, the 86 GB context unchanged).
 constexpr int kPiecePad = 256;
+// Virtual positions behind every unit's keys, for the extra work of the work-group that takes the
+// unit's end: the decode keys' logits are staged in LDS and written out, the appended rows are read
+// from the caller's tensors, marked slots are masked.  Swept 0 / 64 / 96 / 128 (three runs each,
+// one box): Qwen-shaped layer 35.9 / 34.9 / 34.7 / 34.1 us per step, ragged Llama layer 72.0 / 71.9 /
+// 72.1 / 72.1, batch-1 layer 16.0 / 15.8 / 15.9 / 15.9; a surcharge proportional to the decode pool
+// (a quarter of a position per slot and more) helped the Qwen shape as much and cost the ragged
+// Llama layer 1 us and more.
+constexpr int kTailPad = 128;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -474,7 +482,7 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
     const int hp = mq_heads_per_pass(G, q_len);
     passes = (G + hp - 1) / hp;
   }
-  const int P = c->shape.piece_pad;   // positions per unit that stand for the fixed cost of a piece
+  const int P = unit_extra(c->shape);   // virtual positions per unit: the fixed costs of a piece and of a unit's end
   const bool lazy = c->lay.lazy;
   // 1. checks; nothing is changed before all of them have passed
   SeqMask mask;
@@ -697,6 +705,7 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   s.trigger = cfg->evict_trigger; s.S = c->lay.S;
   s.variant = cfg->attn_variant;
   s.piece_pad = kPiecePad;
+  s.tail_pad = kTailPad;
   s.lazy = c->lay.lazy ? 1 : 0;
   s.capw = c->lay.capw;
   const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)s.D);

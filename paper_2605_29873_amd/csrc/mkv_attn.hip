@@ -121,7 +121,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   constexpr int WT = 6144 / (HL * TK);   // decode tiles per logit staging window (24 KiB of LDS)
   constexpr int SK = WT * TK;            // keys per window
   __shared__ float sm_logit[HL][SK];
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1 + s.piece_pad, offs, lane);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1 + unit_extra(s), offs, lane);
   __syncthreads();
   if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -167,14 +167,14 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
     // stand for what starting a piece costs, so that a work-group whose range crosses a unit
     // boundary gets that many keys fewer.  A range that ends inside them has no keys of the unit
     // and leaves no partial.
-    const int Lp = L + s.piece_pad;
+    const int Lp = L + unit_extra(s);                   // (and tail_pad positions behind the keys)
     const int ul = (int)((r0 - offs[b]) / Lp);          // unit inside the sequence
     const int g = ul / s.passes;
     const int pass = ul - g * s.passes;
     const int kav = (int)(r0 - offs[b] - (long long)ul * Lp);
     const int kev = (int)min((long long)Lp, kav + (r1 - r0));
-    const int ka = max(kav - s.piece_pad, 0);           // first key of the piece in the unit
-    const int ke = max(kev - s.piece_pad, 0);           // one past its last key
+    const int ka = min(max(kav - s.piece_pad, 0), L);   // first key of the piece in the unit
+    const int ke = min(max(kev - s.piece_pad, 0), L);   // one past its last key
     if (ke <= ka) {
       r0 += kev - kav;
       continue;
@@ -522,8 +522,8 @@ __device__ __forceinline__ PieceSpan piece_span(const Shape& s, const long long*
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / s.HL;
   const int ul = g * s.passes + pass;
-  // a unit takes L + piece_pad positions of the flattened axis, its keys after the pad
-  const long long off_u = offs[b] + (long long)ul * (L + s.piece_pad) + s.piece_pad;
+  // a unit takes L + piece_pad + tail_pad positions of the flattened axis, its keys after piece_pad
+  const long long off_u = offs[b] + (long long)ul * (L + unit_extra(s)) + s.piece_pad;
   const long long kf = off_u / R, kl = (off_u + L - 1) / R;
   PieceSpan p;
   p.slot0 = (size_t)kf + (size_t)b * s.Hkv * s.passes + ul;

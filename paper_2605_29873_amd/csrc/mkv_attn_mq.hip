@@ -122,7 +122,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   __shared__ float sm_logit[kWindow + kRows * 4];   // rows of SK + 4 floats (the pad spreads the banks)
   __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
   __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
-  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + s.piece_pad, offs, lane, &a.lens);
+  if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + unit_extra(s), offs, lane, &a.lens);
   __syncthreads();
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -177,13 +177,13 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // stand for what starting a piece costs (prologue, merge), so that a work-group whose range
     // crosses a unit boundary gets that many keys fewer.  A range that ends inside them has no keys
     // of the unit and leaves no partial.
-    const int Lp = L + s.piece_pad;
+    const int Lp = L + unit_extra(s);        // virtual positions in front of the keys and (tail_pad) behind them
     const int ul = uniform((int)((r0 - ob) / Lp));   // (the 64-bit division runs on the vector ALU)
     const int g = ul / a.passes;
     const int pass = ul - g * a.passes;
     const int kav = uniform((int)(r0 - ob - (long long)ul * Lp));
     const int kev = uniform((int)min((long long)Lp, kav + (r1 - r0)));
-    const int ka = max(kav - s.piece_pad, 0), ke = max(kev - s.piece_pad, 0);
+    const int ka = min(max(kav - s.piece_pad, 0), L), ke = min(max(kev - s.piece_pad, 0), L);
     if (ke <= ka) {
       r0 += kev - kav;
       continue;
@@ -567,7 +567,7 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
   const int g = h / s.G, hl = h - g * s.G;
   const int pass = hl / a.HP;
   const int ul = g * a.passes + pass;
-  const long long off_u = off_b + (long long)ul * (L + s.piece_pad) + s.piece_pad;   // the unit's first key on the flattened axis
+  const long long off_u = off_b + (long long)ul * (L + unit_extra(s)) + s.piece_pad;   // the unit's first key on the flattened axis
   long long kf, kl;
   if (a.narrow) {       // (a 64-bit division is a long subroutine, and the loads below wait for it)
     kf = (uint32_t)off_u / (uint32_t)a.R;

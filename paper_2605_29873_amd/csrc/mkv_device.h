@@ -85,8 +85,8 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 
 // Prefix sums of the per-sequence key counts, built by one wave into LDS: offs[b] = number of keys
 // of all units of sequences < b, where a sequence has `units` = Hkv * passes units of
-// L_b = M_b + n_d + n_new keys each (0 for inactive sequences; n_new = tokens appended by the
-// step).  offs has B+1 entries.  With `il` valid the lengths come with the launch arguments.
+// L_b = M_b + n_d + n_new positions each (0 for inactive sequences; n_new = tokens appended by the
+// step plus the unit's virtual positions).  offs has B+1 entries.  With `il` valid the lengths come with the launch arguments.
 __device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& lv, const SeqMask& mask,
                                               int units, int n_new, long long* offs, int lane,
                                               const InlineLens* il = nullptr) {

@@ -41,6 +41,9 @@ struct Shape {
   int trigger;       // the decode step evicts when the pool exceeds this (INT32_MAX: never)
   int variant;       // attention kernel variant (tuning), 0 = default
   int piece_pad;     // positions of the flattened key axis charged to a unit for starting a piece
+  int tail_pad;      // virtual positions behind a unit's keys: the work-group that takes the end of a unit
+                     // -- the decode keys -- also stages and writes their logits and reads the appended
+                     // rows, so it gets that many keys fewer
   int lazy;          // 1: one-token evictions only mark the slot (LayerView::dead) and the rows are
                      //    compacted every few dozen steps; 0: every eviction compacts at once
   int capw;          // 32-bit words of one score vector's slot bitmap (LayerView::dead)
@@ -142,6 +145,10 @@ hipError_t launch_project_append(const Shape& s, const LayerView& lv, const SeqM
                                  int hidden, float rope_theta, hipStream_t st, const KernelTimer* tm = nullptr);
 
 hipError_t configure_kernels();
+
+// Virtual positions of a unit on the flattened key axis beside its M + n1 keys: piece_pad in front
+// of the keys, tail_pad behind them.
+__host__ __device__ inline int unit_extra(const Shape& s) { return s.piece_pad + s.tail_pad; }
 
 inline int head_lanes(int G) { return G == 1 ? 1 : G == 2 ? 2 : G <= 4 ? 4 : 8; }
 

@@ -98,3 +98,40 @@ def test_guard_zones_with_the_fused_producer(mkv):
         assert _guards_intact(buf, lo, hi)
     finally:
         mkv.mkv_destroy(ctx)
+
+
+@pytest.mark.parametrize("G,Hkv,mode", [(4, 2, 0), (7, 2, 1)])
+def test_guard_zones_with_deferred_compaction(mkv, G, Hkv, mode):
+    # the paper's cadence on the matrix-core kernels, default capacity: slot bitmaps, hole counts
+    # and pending selections live in the layer blocks of the arena; two layers, three sequences of
+    # which one pauses, readers (which compact) in between
+    wl = X.Workload("guards-deferred", batch=3, n_layers=2, n_q_heads=G * Hkv, n_kv_heads=Hkv, head_dim=128,
+                    dtype="bf16", prefill_min=5, prefill_max=300, decode_budget=40, evict_trigger=40,
+                    recent_window=4, alpha=0.9, steps=0, hh_prob=0.05)
+    ctx, buf, lo, hi = _guarded_ctx(mkv, wl, score_mode=mode)
+    try:
+        assert _guards_intact(buf, lo, hi)
+        for layer in range(wl.n_layers):
+            for s in range(wl.batch):
+                k, v = X.prefill_kv(wl, layer, s)
+                if k.shape[0]:
+                    dk, dv = to_device(k, "bf16"), to_device(v, "bf16")
+                    mkv.mkv_prefill_append(ctx, layer, s, dk.data_ptr(), dv.data_ptr(), k.shape[0])
+        out = torch.empty((wl.batch, wl.n_q_heads, 128), dtype=torch.bfloat16, device="cuda")
+        marked = 0
+        for t in range(160):
+            mask = np.array([1, t % 4 != 1, 1], dtype=np.uint8)
+            for layer in range(wl.n_layers):
+                q, k, v = (to_device(a, "bf16") for a in X.step_batch(wl, layer, t))
+                mkv.mkv_decode_step(ctx, layer, q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), mask)
+            _, _, live, _ = mkv.mkv_read_slots(ctx, 1, 2, 256)
+            marked = max(marked, int((~live).sum()))
+            if t % 45 == 44:
+                mkv.mkv_read_scores(ctx, 0, 0)
+                mkv.mkv_read_kv(ctx, 1, 2, 0, 1, 128, mkv.MKV_BF16)
+        assert marked >= 5 and torch.isfinite(out.float()).all()
+        for layer in range(wl.n_layers):
+            assert mkv.mkv_get_lens(ctx, layer, 0)[1] == 40
+        assert _guards_intact(buf, lo, hi)
+    finally:
+        mkv.mkv_destroy(ctx)
