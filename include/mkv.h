@@ -91,8 +91,8 @@ typedef struct {
   float   softmax_scale;   /* 0 => 1/sqrt(head_dim)                                              */
   int32_t score_mode;      /* mkv_score_mode                                                     */
   int32_t split_keys;      /* tuning: length of the key range one attention work-group takes (multiple
-                              of 16, >= 64; every (sequence, KV head) unit counts 384 positions more
-                              than its keys: 256 in front for the cost of starting on it, 128 behind
+                              of 16, >= 64; every (sequence, KV head) unit counts 320 positions more
+                              than its keys: 192 in front for the cost of starting on it, 128 behind
                               for the extra work at its end); 0 => chosen per step so that the launch
                               just fills the chip                                               */
   int32_t attn_variant;    /* tuning: attention kernel variant; 0 => library default (the

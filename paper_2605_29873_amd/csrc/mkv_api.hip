@@ -52,10 +52,12 @@ constexpr size_t kAlign = 256;
 constexpr int kMaxGroups = 4096;          // attention work-groups per launch, at most
 // Positions of the flattened key axis charged to every unit for the fixed cost of starting a piece
 // (prologue, merge): a work-group whose range crosses a unit boundary gets that many keys fewer,
-// which evens out the finishing times.  Measured over 0..512: 256 is best or within noise on every
-// workload (batch-1 Llama layer 11.4 -> 9.0 us attention, Qwen-shaped layer 26.7 -> 25.0 us,
-// ragged Llama layer 63.9 -> 63.1 us, the 86 GB context unchanged).
-constexpr int kPiecePad = 256;
+// which evens out the finishing times.  Against no charge at all: batch-1 Llama layer 11.4 -> 9.0 us
+// attention, Qwen-shaped layer 26.7 -> 25.0 us, ragged Llama layer 63.9 -> 63.1 us, the 86 GB
+// context unchanged.  Swept again 128 .. 512 beside the tail pad below (two runs each, one box):
+// ragged Llama layer 71.7 / 71.9 / 72.2 / 72.4 / 72.9 / 73.0 us per step at 128 / 192 / 256 / 320 /
+// 384 / 512, Qwen-shaped layer 34.4 / 33.9 / 34.0 / 34.0 / 34.3 / 34.5, batch-1 layer flat.
+constexpr int kPiecePad = 192;
 // Virtual positions behind every unit's keys, for the extra work of the work-group that takes the
 // unit's end: the decode keys' logits are staged in LDS and written out, the appended rows are read
 // from the caller's tensors, marked slots are masked.  Swept 0 / 64 / 96 / 128 (three runs each,
