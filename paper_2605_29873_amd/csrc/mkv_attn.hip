@@ -122,6 +122,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_split_kernel(const AttnArgs a) 
   constexpr int SK = WT * TK;            // keys per window
   __shared__ float sm_logit[HL][SK];
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, 1 + unit_extra(s), offs, lane);
+  else if (wave == 1) warm_kernel_arguments<sizeof(AttnArgs)>();   // meanwhile, for all waves of the compute unit
   __syncthreads();
   if (blockIdx.x == 0) {  // bookkeeping for the finishing kernel
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -538,6 +539,7 @@ __device__ __forceinline__ PieceSpan piece_span(const Shape& s, const long long*
 // head mean (Eq. 4) and apply I <- alpha*I + abar (Eq. 5), with I = 0 for the new slot (Eq. 6).
 template <int D>
 __global__ __launch_bounds__(kFinishThreads) void finish_kernel(const FinishArgs a) {
+  warm_kernel_arguments<sizeof(FinishArgs)>();
   const Shape& s = a.s;
   const int b = blockIdx.y;
   if (!a.mask.active(b)) return;

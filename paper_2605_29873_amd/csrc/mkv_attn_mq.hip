@@ -123,6 +123,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
   __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + unit_extra(s), offs, lane, &a.lens);
+  else if (wave == 1) warm_kernel_arguments<sizeof(MqArgs)>();   // meanwhile, for all waves of the compute unit
   __syncthreads();
   if (blockIdx.x == 0) {
     for (int b = tid; b <= s.B; b += kThreads) {
@@ -597,6 +598,7 @@ __device__ __forceinline__ RowSpan row_span(const FinishMqArgs& a, long long off
 // carries none of its loads and tests.
 template <bool ONE, bool LAZY>
 __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishMqArgs a) {
+  warm_kernel_arguments<sizeof(FinishMqArgs)>();
   const Shape& s = a.s;
   const int b = blockIdx.y;
   if (!a.mask.active(b)) return;

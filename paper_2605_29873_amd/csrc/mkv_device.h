@@ -59,6 +59,21 @@ __device__ __forceinline__ float across_groups_sum(float x) {
 // Values that are equal in every lane of a wave but that the compiler cannot know to be (read
 // from LDS or through a lane-indexed path): moving them to scalar registers keeps the address and
 // loop arithmetic derived from them off the vector ALU.
+// Brings every 64-byte line of the kernel's argument block (BYTES long) into the scalar cache with
+// independent loads and one wait.  The compiler fetches arguments where they are first used, in
+// several batches that each wait for memory; with a large argument block the batches touch one new
+// line after the other and their round trips add up in front of the first key load.  After this
+// call they hit the cache.
+template <int BYTES>
+__device__ __forceinline__ void warm_kernel_arguments() {
+  typedef const __attribute__((address_space(4))) uint32_t* arg_words_t;
+  arg_words_t words = (arg_words_t)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t any = 0;
+#pragma unroll
+  for (int line = 0; line < BYTES / 64; ++line) any |= words[line * 16];
+  asm volatile("" ::"s"(any));
+}
+
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 __device__ __forceinline__ long long uniform(long long x) {
   const uint32_t lo = __builtin_amdgcn_readfirstlane((int)(uint32_t)x);
