@@ -229,22 +229,29 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
 
     // Append (Alg. 1): the work-group whose piece holds new slots stores their rows for later
     // steps; in this step every reader takes them from k_new / v_new.
-    if (pass == 0) {
-      for (int idx = tid; idx < (in_pool ? 0 : (d1 - a0) * 2 * kNV); idx += kThreads) {
-        const int row = idx / (2 * kNV), rem = idx - row * 2 * kNV;
-        const int vsel = rem / kNV, vec = rem - vsel * kNV;
-        const int jn = a0 + row;
-        const char* src = (vsel ? vnew : knew) + (size_t)(jn - n0) * new_stride + vec * 16;
-        char* dst = (char*)(vsel ? a.lv.Vd : a.lv.Kd) + (head_row * (size_t)s.dstride + (size_t)jn) * kRowB + vec * 16;
-        *reinterpret_cast<uint4*>(dst) = ldg16(src);
+    auto append_rows = [&]() __attribute__((always_inline)) {
+      if (pass == 0) {
+        for (int idx = tid; idx < (in_pool ? 0 : (d1 - a0) * 2 * kNV); idx += kThreads) {
+          const int row = idx / (2 * kNV), rem = idx - row * 2 * kNV;
+          const int vsel = rem / kNV, vec = rem - vsel * kNV;
+          const int jn = a0 + row;
+          const char* src = (vsel ? vnew : knew) + (size_t)(jn - n0) * new_stride + vec * 16;
+          char* dst = (char*)(vsel ? a.lv.Vd : a.lv.Kd) + (head_row * (size_t)s.dstride + (size_t)jn) * kRowB + vec * 16;
+          *reinterpret_cast<uint4*>(dst) = ldg16(src);
+        }
+        if (g == 0 || s.S > 1) {     // positions: one vector per sequence, or one per KV head
+          const int t0 = a.lv.tpos[b];
+          const size_t vec = (size_t)b * s.S + (s.S > 1 ? g : 0);
+          for (int idx = tid; idx < d1 - a0; idx += kThreads)
+            a.lv.pos[vec * s.cap + a0 + idx] = t0 + (a0 + idx - n0);
+        }
       }
-      if (g == 0 || s.S > 1) {     // positions: one vector per sequence, or one per KV head
-        const int t0 = a.lv.tpos[b];
-        const size_t vec = (size_t)b * s.S + (s.S > 1 ? g : 0);
-        for (int idx = tid; idx < d1 - a0; idx += kThreads)
-          a.lv.pos[vec * s.cap + a0 + idx] = t0 + (a0 + idx - n0);
-      }
-    }
+    };
+    // Where it runs: after the first tile has been requested (everything of the piece that waits for
+    // memory then arrives in one round trip) -- except with deferred compaction, whose instantiation
+    // has no registers to spare for tile registers that live outside the tile loop.
+    constexpr bool kEarly = !LAZY;
+    if constexpr (!kEarly) append_rows();
 
     // query rows: row r = (head inside the pass) * Q + (query position); this lane serves rows
     // r16 + 16 * nb
@@ -440,12 +447,16 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // wave always has loads in flight.
     // `masked`: the piece holds keys of the decode pool, whose slots may be marked (LAZY only); a
     // piece of prompt keys alone runs the plain loop
-    auto run_tiles = [&](int t_lo, int t_hi, auto masked) __attribute__((always_inline)) {
-      uint4 kbuf[2][4], vbuf[2][4];
-      int tt = t_lo + wave;
-      uint32_t dmask = load_dead(tt, t_hi, masked);
+    // requests a wave's first tile of [t_lo, t_hi); returns the tile's bitmap bits
+    auto prime = [&](int t_lo, int t_hi, auto masked, uint4 (&kbuf)[2][4], uint4 (&vbuf)[2][4]) __attribute__((always_inline)) {
+      const int tt = t_lo + wave;
+      const uint32_t bits = load_dead(tt, t_hi, masked);
       load_k(tt, t_hi, kbuf);
       load_v(tt, t_hi, vbuf);
+      return bits;
+    };
+    auto tile_loop = [&](int t_lo, int t_hi, auto masked, uint32_t dmask, uint4 (&kbuf)[2][4], uint4 (&vbuf)[2][4]) __attribute__((always_inline)) {
+      int tt = t_lo + wave;
       while (tt < t_hi) {
         float x[NB][8];
         score_tile(tt, kbuf, dmask, masked, x);
@@ -459,14 +470,30 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
         tt += WPB;
       }
     };
+    // kEarly: the tile registers live at piece scope, and the first window's first tile (`primed`)
+    // is already under way when its loop starts
+    [[maybe_unused]] uint4 kbuf0[2][4], vbuf0[2][4];
+    auto run_tiles = [&](int t_lo, int t_hi, auto masked, [[maybe_unused]] bool primed) __attribute__((always_inline)) {
+      if constexpr (kEarly) {
+        uint32_t dmask = 0u;
+        if (!primed) dmask = prime(t_lo, t_hi, masked, kbuf0, vbuf0);
+        tile_loop(t_lo, t_hi, masked, dmask, kbuf0, vbuf0);
+      } else {
+        uint4 kbuf[2][4], vbuf[2][4];
+        const uint32_t dmask = prime(t_lo, t_hi, masked, kbuf, vbuf);
+        tile_loop(t_lo, t_hi, masked, dmask, kbuf, vbuf);
+      }
+    };
 
     // phases: all prefill tiles plus the first window of pool tiles, then one window per phase (the
     // tile of appended tokens rides with the last); the staged logits of a window are written out
     // by the whole work-group
+    if constexpr (kEarly) (void)prime(0, min(ntile, ntp + WT), std::false_type{}, kbuf0, vbuf0);
+    if constexpr (kEarly) append_rows();
     for (int t_lo = 0; t_lo < ntile; ++win) {
       const int t_hi = min(ntile, ntp + (win + 1) * WT);
-      if (LAZY && ntd > 0) run_tiles(t_lo, t_hi, std::true_type{});
-      else run_tiles(t_lo, t_hi, std::false_type{});
+      if (LAZY && ntd > 0) run_tiles(t_lo, t_hi, std::true_type{}, false);
+      else run_tiles(t_lo, t_hi, std::false_type{}, kEarly && t_lo == 0);
       const int wk0 = win * SK;
       const int nk = min(dp - d0 - wk0, SK);
       const bool last = t_hi == ntile;
