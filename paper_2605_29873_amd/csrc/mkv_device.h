@@ -59,19 +59,49 @@ __device__ __forceinline__ float across_groups_sum(float x) {
 // Values that are equal in every lane of a wave but that the compiler cannot know to be (read
 // from LDS or through a lane-indexed path): moving them to scalar registers keeps the address and
 // loop arithmetic derived from them off the vector ALU.
-// Brings every 64-byte line of the kernel's argument block (BYTES long) into the scalar cache with
-// independent loads and one wait.  The compiler fetches arguments where they are first used, in
-// several batches that each wait for memory; with a large argument block the batches touch one new
-// line after the other and their round trips add up in front of the first key load.  After this
-// call they hit the cache.
+// Brings every 64-byte line of the kernel's argument block (BYTES long, at most 1 KiB) into the
+// scalar cache with independent loads and one wait.  The compiler fetches arguments where they are
+// first used, in several batches that each wait for memory; with a large argument block the batches
+// touch one new line after the other and their round trips add up in front of the first key load.
+// After this call they hit the cache.
+// Written as two blocks of eight scalar loads with the wait at the end of the second: left to the
+// compiler the loads come in two batches with a wait after each.  The first block's registers are
+// operands of the second, so nothing else is allocated to them while their loads are in flight.
 template <int BYTES>
 __device__ __forceinline__ void warm_kernel_arguments() {
-  typedef const __attribute__((address_space(4))) uint32_t* arg_words_t;
-  arg_words_t words = (arg_words_t)__builtin_amdgcn_kernarg_segment_ptr();
-  uint32_t any = 0;
-#pragma unroll
-  for (int line = 0; line < BYTES / 64; ++line) any |= words[line * 16];
-  asm volatile("" ::"s"(any));
+  static_assert(BYTES >= 64 && BYTES <= 1024, "argument block of one to sixteen lines");
+  // line i is touched through its first word, which lies inside the block
+#define MKV_LINE(i) ((i) * 64 + 4 <= BYTES ? (i) * 64 : 0)
+  const uint64_t base = (uint64_t)__builtin_amdgcn_kernarg_segment_ptr();
+  uint32_t t0, t1, t2, t3, t4, t5, t6, t7;
+  asm volatile(
+      "s_load_dword %0, %8, %9\n\t"
+      "s_load_dword %1, %8, %10\n\t"
+      "s_load_dword %2, %8, %11\n\t"
+      "s_load_dword %3, %8, %12\n\t"
+      "s_load_dword %4, %8, %13\n\t"
+      "s_load_dword %5, %8, %14\n\t"
+      "s_load_dword %6, %8, %15\n\t"
+      "s_load_dword %7, %8, %16"
+      : "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
+      : "s"(base), "i"(MKV_LINE(0)), "i"(MKV_LINE(1)), "i"(MKV_LINE(2)), "i"(MKV_LINE(3)), "i"(MKV_LINE(4)),
+        "i"(MKV_LINE(5)), "i"(MKV_LINE(6)), "i"(MKV_LINE(7)));
+  uint32_t u0, u1, u2, u3, u4, u5, u6, u7;
+  asm volatile(
+      "s_load_dword %0, %16, %17\n\t"
+      "s_load_dword %1, %16, %18\n\t"
+      "s_load_dword %2, %16, %19\n\t"
+      "s_load_dword %3, %16, %20\n\t"
+      "s_load_dword %4, %16, %21\n\t"
+      "s_load_dword %5, %16, %22\n\t"
+      "s_load_dword %6, %16, %23\n\t"
+      "s_load_dword %7, %16, %24\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(u0), "=&s"(u1), "=&s"(u2), "=&s"(u3), "=&s"(u4), "=&s"(u5), "=&s"(u6), "=&s"(u7), "+s"(t0), "+s"(t1),
+        "+s"(t2), "+s"(t3), "+s"(t4), "+s"(t5), "+s"(t6), "+s"(t7)
+      : "s"(base), "i"(MKV_LINE(8)), "i"(MKV_LINE(9)), "i"(MKV_LINE(10)), "i"(MKV_LINE(11)), "i"(MKV_LINE(12)),
+        "i"(MKV_LINE(13)), "i"(MKV_LINE(14)), "i"(MKV_LINE(15)));
+#undef MKV_LINE
 }
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
