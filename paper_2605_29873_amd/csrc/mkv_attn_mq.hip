@@ -661,7 +661,9 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     constexpr int kPrePieces = 16;
     float2 pre[kPrePieces];
 #pragma unroll
-    for (int i = 0; i < kPrePieces; ++i) pre[i] = i < ns ? po[(size_t)i * ostride] : make_float2(0.f, 0.f);
+    // (every load unconditional -- a piece index past the end re-reads the last piece and gets no
+    // weight below: a predicate per load is a branch out of line and back per load)
+    for (int i = 0; i < kPrePieces; ++i) pre[i] = po[(size_t)min(i, ns - 1) * ostride];
     float mx, L, m_first;                // m_first: reference of piece `lane`
     wave_merge_ml(ml, mlstride, ns, lane, mx, L, &m_first);
     float2 o = make_float2(0.f, 0.f);
@@ -723,11 +725,17 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
     if constexpr (ONE) {
       const float* lg0 = a.sc.logits + logit_index(s, b, rows, 0, j);
 #pragma unroll
-      for (int h = 0; h < kPre; ++h) xpre[h] = h < s.H ? lg0[h * kLogitTile] : 0.f;
+      // (unconditional as well; heads past H - 1 repeat the last head and are never summed)
+      for (int h = 0; h < kPre; ++h) xpre[h] = lg0[min(h, s.H - 1) * kLogitTile];
     }
+    ipre[0] = j < n0 ? a.lv.score[(size_t)b * s.S * s.cap + j] : 0.f;
 #pragma unroll
-    for (int sv = 0; sv < kPreS; ++sv)
-      ipre[sv] = (sv < s.S && j < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + j] : 0.f;
+    for (int sv = 1; sv < kPreS; ++sv) ipre[sv] = 0.f;
+    if (s.S > 1) {       // one vector per KV head: their previous values too
+#pragma unroll
+      for (int sv = 1; sv < kPreS; ++sv)
+        ipre[sv] = (sv < s.S && j < n0) ? a.lv.score[((size_t)b * s.S + sv) * s.cap + j] : 0.f;
+    }
   }
   // ONE: every wave rebuilds the (at most 32) normalisers by itself, in registers: lane l takes
   // row l % 32 and the pieces of parity l / 32, the two halves meet through one lane exchange, and
