@@ -179,8 +179,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // crosses a unit boundary gets that many keys fewer.  A range that ends inside them has no keys
     // of the unit and leaves no partial.
     const int Lp = L + unit_extra(s);        // virtual positions in front of the keys and (tail_pad) behind them
-    const int ul = uniform((int)((r0 - ob) / Lp));   // (the 64-bit division runs on the vector ALU)
-    const int g = ul / a.passes;
+    // (a 64-bit division is a long subroutine on the vector ALU; distances below 2^22 take the short way)
+    const long long rel = r0 - ob;
+    const int ul = uniform(rel < (1 << 22) ? div_small((int)rel, Lp) : (int)(rel / Lp));
+    const int g = a.passes == 1 ? ul : uniform(div_small(ul, a.passes));
     const int pass = ul - g * a.passes;
     const int kav = uniform((int)(r0 - ob - (long long)ul * Lp));
     const int kev = uniform((int)min((long long)Lp, kav + (r1 - r0)));
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     const int ntile = ntp + ntd + nta;
     const int nrows = min(a.HP, s.G - pass * a.HP) * Q;   // real rows of this pass
     // logit staging window: as many keys as the real rows leave room for (whole tiles)
-    const int SK = (kWindow / nrows) & ~(kTK - 1);
+    const int SK = uniform(div_small(kWindow, nrows)) & ~(kTK - 1);
     const int WT = SK / kTK;
     const int SKP = SK + 4;
 
@@ -260,7 +262,7 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       const int rr = r16 + 16 * nb;
-      const int hl = rr / Q;
+      const int hl = Q == 1 ? rr : div_small(rr, Q);
       qi[nb] = rr - hl * Q;
       const bool row_ok = rr < nrows;
       const char* qp = a.q + (((size_t)b * Q + qi[nb]) * s.H + g * s.G + pass * a.HP + hl) * kRowB;

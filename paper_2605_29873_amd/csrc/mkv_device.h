@@ -163,6 +163,15 @@ __device__ __forceinline__ void build_offsets(const Shape& s, const LayerView& l
   if (lane == 63) offs[s.B] = incl;
 }
 
+// floor(a / b) for 0 <= a < 2^22 and b >= 1 through the float reciprocal and one correction step
+// (the integer division is a subroutine of some forty instructions, this is ten).
+__device__ __forceinline__ int div_small(int a, int b) {
+  int q = (int)((float)a * __frcp_rn((float)b));      // off by one at most
+  const int r = a - q * b;
+  q += (r >= b) - (r < 0);
+  return q;
+}
+
 // quad_perm controls that exchange lane i with lane i^K inside every group of four lanes
 template <int K>
 __device__ __forceinline__ float quad_xor(float x) {
