@@ -315,19 +315,17 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
       t.vv = pick(seg == 2, vv_new, vv_pool);
       return t;
     };
-    // the 32 bitmap bits of a tile of pool keys (bit i: key i of the tile is an evicted slot); the
-    // load is unconditional like the others (word 0 for tiles that need none)
+    // the two bitmap words that hold the 32 bits of a tile of pool keys (bit i of the tile: key i is
+    // an evicted slot); the loads are unconditional like the others (words 0 and 1 for tiles that
+    // need none).  The words are cut to the tile's 32 bits only where they are used, a tile later:
+    // combined here, the wait for them also held back the next tile's key loads.
     auto load_dead = [&](int tt, int t_end, auto masked) __attribute__((always_inline)) {
-      if constexpr (!LAZY || !decltype(masked)::value) return 0u;
+      if constexpr (!LAZY || !decltype(masked)::value) return make_uint2(0u, 0u);
       else {
         const int seg = tile_seg(tt);
         const int jb = tile_key(tt, seg);
-        const bool pool_tile = seg == 1 && tt < t_end;
-        const int wi = pool_tile ? (jb >> 5) : 0;
-        const uint32_t w0 = deadw[wi], w1 = deadw[wi + 1];     // the bitmap has two spare words
-        const uint32_t sh = (uint32_t)jb & 31u;
-        const uint32_t m = sh ? ((w0 >> sh) | (w1 << (32u - sh))) : w0;
-        return pool_tile ? m : 0u;
+        const int wi = (seg == 1 && tt < t_end) ? (jb >> 5) : 0;
+        return make_uint2(deadw[wi], deadw[wi + 1]);           // the bitmap has two spare words
       }
     };
     auto load_k = [&](int tt, int t_end, uint4 (&kr)[2][4]) __attribute__((always_inline)) {
@@ -353,9 +351,10 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     constexpr float kSlack = 8.0f;
     // scores of one tile against the rows of each block: x[nb][4h + i] = logit of key 16h + 4j + i (base 2), -inf
     // where masked; decode logits are staged for the score update
-    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], uint32_t dmask, auto masked, float (&x)[NB][8]) __attribute__((always_inline)) {
+    auto score_tile = [&](int tt, const uint4 (&kr)[2][4], uint2 dwords, auto masked, float (&x)[NB][8]) __attribute__((always_inline)) {
       const int seg = tile_seg(tt);
       const int jb = tile_key(tt, seg);
+      [[maybe_unused]] const uint32_t dmask = __builtin_amdgcn_alignbit(dwords.y, dwords.x, (uint32_t)jb & 31u);
       const int jn = pick3(seg, p1, dp, d1);
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
@@ -452,12 +451,12 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // requests a wave's first tile of [t_lo, t_hi); returns the tile's bitmap bits
     auto prime = [&](int t_lo, int t_hi, auto masked, uint4 (&kbuf)[2][4], uint4 (&vbuf)[2][4]) __attribute__((always_inline)) {
       const int tt = t_lo + wave;
-      const uint32_t bits = load_dead(tt, t_hi, masked);
+      const uint2 bits = load_dead(tt, t_hi, masked);
       load_k(tt, t_hi, kbuf);
       load_v(tt, t_hi, vbuf);
       return bits;
     };
-    auto tile_loop = [&](int t_lo, int t_hi, auto masked, uint32_t dmask, uint4 (&kbuf)[2][4], uint4 (&vbuf)[2][4]) __attribute__((always_inline)) {
+    auto tile_loop = [&](int t_lo, int t_hi, auto masked, uint2 dmask, uint4 (&kbuf)[2][4], uint4 (&vbuf)[2][4]) __attribute__((always_inline)) {
       int tt = t_lo + wave;
       while (tt < t_hi) {
         float x[NB][8];
@@ -477,12 +476,12 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     [[maybe_unused]] uint4 kbuf0[2][4], vbuf0[2][4];
     auto run_tiles = [&](int t_lo, int t_hi, auto masked, [[maybe_unused]] bool primed) __attribute__((always_inline)) {
       if constexpr (kEarly) {
-        uint32_t dmask = 0u;
+        uint2 dmask = make_uint2(0u, 0u);
         if (!primed) dmask = prime(t_lo, t_hi, masked, kbuf0, vbuf0);
         tile_loop(t_lo, t_hi, masked, dmask, kbuf0, vbuf0);
       } else {
         uint4 kbuf[2][4], vbuf[2][4];
-        const uint32_t dmask = prime(t_lo, t_hi, masked, kbuf, vbuf);
+        const uint2 dmask = prime(t_lo, t_hi, masked, kbuf, vbuf);
         tile_loop(t_lo, t_hi, masked, dmask, kbuf, vbuf);
       }
     };
