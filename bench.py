@@ -12,10 +12,14 @@ tokens/s and the whole-step algorithmic GB/s beside it; `roofline` covers the at
 timed with start/stop HIP events attached to every launch in a second pass of the same steps; `cpu_baseline` is the
 CPU oracle timed on a bounded sample of the same workload.
 
-The metric is the step *with* its share of evictions, so the timed region always consists of whole
-eviction cycles: --steps is rounded up to a multiple of the workload's eviction chunk (64 for the
-Llama-shaped layers, 1 for the Qwen-shaped one) and the count actually timed is reported as
-`steps_timed`.  Any such window holds the same number of evictions wherever it starts.
+The metric is the step *with* its share of evictions in steady state, so the timed region always
+consists of whole eviction cycles: --steps is rounded up to a multiple of the workload's eviction
+cycle (64 steps for the Llama-shaped layers, 65 with deferred compaction for the Qwen-shaped one), for
+the single-layer workloads to at least four cycles, and the count actually timed is reported as
+`steps_timed`.  Any such window holds the same number of evictions wherever it starts.  The
+warm-up is --warmup steps but at least one whole cycle (reported as `warmup_run`), so that the
+first eviction of the process and the first calls through the binding lie in front of the timed
+region: a 64-step window (4.5 ms) right after five warm-up calls read 1-3 us per step high.
 """
 from __future__ import annotations
 
@@ -254,10 +258,18 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
     job = Job(wl, split_keys, variant, gpc, q_len)
     nq = max(1, q_len)
     requested = steps
+    warmup_run = warmup
     if evicts:
         steps = whole_cycles(wl, steps, q_len, variant)
+        if wl.n_layers == 1:
+            # steady state (cf. the docstring): the warm-up passes the first eviction, and the timed
+            # region is at least four whole cycles -- a window of a few milliseconds right after a
+            # handful of warm-up calls mostly measures the host getting up to speed
+            cycle = whole_cycles(wl, 1, q_len, variant)
+            steps = max(steps, 4 * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 256, q_len, variant))
+            warmup_run = max(warmup, cycle + 8)
     try:
-        run_steps(job, warmup)
+        run_steps(job, warmup_run)
         n_now = pool_sizes(job)
         total_bytes, _, evict_steps, n_after = simulate(job, n_now, steps)
         gpu_s, wall_s = time_region(job, steps)
@@ -281,6 +293,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
             "workload": wl.name,
             "steps_requested": requested,
             "steps_timed": steps,
+            "warmup_run": warmup_run,
             "evicting_steps_in_timed_window": evict_steps,
             "deferred_compaction": bool(deferred and finite),
             "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
@@ -491,7 +504,8 @@ def main():
         "value": main_res["us_per_step_per_layer"],
         "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "steps_timed": main_res["steps_timed"],      # --steps rounded up to whole eviction cycles
+        "steps_timed": main_res["steps_timed"],      # --steps rounded up to whole eviction cycles, at least four
+        "warmup_run": main_res["warmup_run"],        # --warmup, at least one whole eviction cycle
         "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl.dtype == "f32" else "bf16",   # bf16 operands, fp32 accumulation and scores
