@@ -190,7 +190,17 @@ int mkv_decode_step(mkv_ctx* ctx, int layer, const void* q, const void* k_new, c
  *     earlier in the same call.  Two calls that overlap in time on one GPU (different streams)
  *     race on it: keep them on one stream or order them.
  *   - mkv_read_probs after this call reads the array, so it is only valid until the next
- *     mkv_decode_step_static on that GPU. */
+ *     mkv_decode_step_static on that GPU.
+ *   - The GPU the context was created on must be the current one (MKV_ERR_STATE otherwise): each
+ *     GPU has its own copy of the array.
+ *   - Under stream capture: a step's launches carry the pool sizes the host side holds at the time
+ *     of the call (launch geometry, and for batches up to 32 the lengths themselves), so a captured
+ *     step may only be replayed on pools of those sizes.  In steady state the sizes recur after one
+ *     whole eviction cycle -- evict_trigger - decode_budget + 1 steps, or with deferred compaction
+ *     the spare slots + 1 -- so capture whole cycles, with the same active sequences in every call
+ *     of a cycle, and replay the graph from the state it was captured at (mkv_decode_step can be
+ *     captured the same way).  No reader (mkv_read_scores, mkv_read_kv, ...) may compact a pool
+ *     between two replays of a graph captured with deferred compaction; mkv_read_slots does not. */
 #define MKV_STATIC_SCRATCH_BYTES (32u << 20)
 int mkv_decode_step_static(mkv_ctx* ctx, int layer, const void* q, const void* k_new, const void* v_new,
                            void* out, const uint8_t* seq_mask);

@@ -30,12 +30,13 @@ constexpr int kMaxDevices = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once
 
-// Device address of the static scratch array on the current GPU.
-hipError_t static_scratch_base(char** out) {
+// Device address of the static scratch array on the current GPU (*dev_out: which one that is).
+hipError_t static_scratch_base(char** out, int* dev_out = nullptr) {
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (dev_out) *dev_out = dev;
   std::lock_guard<std::mutex> lock(g_scratch_mutex);
   if (!g_scratch_ptr[dev]) {
     void* p = nullptr;
@@ -262,6 +263,7 @@ struct mkv_ctx {
   Layout lay;
   Shape shape;
   hipStream_t stream;
+  int device;            // the GPU that was current in mkv_create: arena, stream and kernels live there
   char* arena;
   bool own_arena;
   // [L*B]; h_nd: decode slots in use, of which h_holes hold evicted tokens that await compaction
@@ -531,8 +533,12 @@ int step(mkv_ctx* c, int layer, int q_len, bool mq, const void* q, const void* k
   };
   char* static_base = nullptr;
   if (static_scratch) {
-    hipError_t se = static_scratch_base(&static_base);
+    int dev_now = -1;
+    hipError_t se = static_scratch_base(&static_base, &dev_now);
     if (se != hipSuccess) return fail_hip(c, se, "address of the static scratch array");
+    // every GPU has its own copy of the array: the one of another GPU is no memory of this context's
+    if (dev_now != c->device)
+      return fail(c, MKV_ERR_STATE, fmt("GPU %d is current, the context was created on GPU %d", dev_now, c->device));
     // does the step's scratch fit?  Decided here, before anything is enqueued, on the slots in use
     // now: a compaction below can only shorten the key axis
     long long total_now = 0, R_now = 0;
@@ -719,9 +725,10 @@ int mkv_create(const mkv_config* cfg, mkv_ctx** out) {
   c->probs_compacted.assign(cfg->batch, 0);
   c->last_sc = scratch_view(c);
   hipError_t e = configure_kernels();
+  c->device = -1;
   if (e == hipSuccess) {   // address of the static scratch array on this GPU, for mkv_decode_step_static
     char* base = nullptr;
-    e = static_scratch_base(&base);
+    e = static_scratch_base(&base, &c->device);
   }
   {
     int dev = 0, cus = 256;
