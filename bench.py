@@ -15,8 +15,9 @@ CPU oracle timed on a bounded sample of the same workload.
 The metric is the step *with* its share of evictions in steady state, so the timed region always
 consists of whole eviction cycles: --steps is rounded up to a multiple of the workload's eviction
 cycle (64 steps for the Llama-shaped layers, 65 with deferred compaction for the Qwen-shaped one), for
-the single-layer workloads to at least four cycles, and the count actually timed is reported as
-`steps_timed`.  Any such window holds the same number of evictions wherever it starts.  The
+the single-layer workloads to at least sixteen cycles (1024 steps and more; the mean over the whole
+region is `value`, the median over its cycles is reported beside it), and the count actually timed
+is reported as `steps_timed`.  Any such window holds the same number of evictions wherever it starts.  The
 warm-up is --warmup steps but at least one whole cycle (reported as `warmup_run`), so that the
 first eviction of the process and the first calls through the binding lie in front of the timed
 region: a 64-step window (4.5 ms) right after five warm-up calls read 1-3 us per step high.
@@ -36,6 +37,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+# Single-layer workloads: whole eviction cycles timed at least (16 cycles of 64 steps = 1024 steps).
+kMinCycles = 16
 
 # Kernel arguments in device memory: the default of this ROCm release, stated here because the
 # kernels' start-up depends on it (with the arguments in host memory every launch waits for them
@@ -197,17 +200,24 @@ def algorithmic_bytes(job: Job, n_d_before: list[int]):
     return attn + rest, attn
 
 
-def time_region(job: Job, steps: int):
+def time_region(job: Job, steps: int, window: int = 0):
+    """Times `steps` steps between two events on the library's stream.  window > 0: an event is
+    also recorded after every `window` steps (whole eviction cycles), and the per-window times come
+    back as microseconds per step per layer (one event per cycle: well under 0.1 us per step)."""
     torch = job.torch
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_win = steps // window if window and steps % window == 0 else 1
+    per = steps // n_win
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_win + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    e0.record()
-    run_steps(job, steps)
-    e1.record()
+    evs[0].record()
+    for w in range(n_win):
+        run_steps(job, per)
+        evs[w + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    return e0.elapsed_time(e1) * 1e-3, wall
+    windows = [evs[w].elapsed_time(evs[w + 1]) * 1e3 / (per * job.wl.n_layers) for w in range(n_win)]
+    return evs[0].elapsed_time(evs[-1]) * 1e-3, wall, windows
 
 
 def deferred_compaction(wl, q_len=0, variant=0):
@@ -266,13 +276,14 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
             # region is at least four whole cycles -- a window of a few milliseconds right after a
             # handful of warm-up calls mostly measures the host getting up to speed
             cycle = whole_cycles(wl, 1, q_len, variant)
-            steps = max(steps, 4 * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 256, q_len, variant))
+            steps = max(steps, kMinCycles * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 1024, q_len, variant))
             warmup_run = max(warmup, cycle + 8)
     try:
         run_steps(job, warmup_run)
         n_now = pool_sizes(job)
         total_bytes, _, evict_steps, n_after = simulate(job, n_now, steps)
-        gpu_s, wall_s = time_region(job, steps)
+        cycle = whole_cycles(wl, 1, q_len, variant) if evicts else 0
+        gpu_s, wall_s, windows = time_region(job, steps, cycle if cycle >= 16 else 0)
         assert pool_sizes(job) == n_after, "the pools did not move as the byte count assumes"
         # second pass of the same number of steps with per-kernel events; its attention bytes are
         # counted for the pool sizes of that pass
@@ -297,6 +308,10 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
             "evicting_steps_in_timed_window": evict_steps,
             "deferred_compaction": bool(deferred and finite),
             "us_per_step_per_layer": gpu_s * 1e6 / n_launch,
+            # the same region cut into whole eviction cycles: median, fastest and slowest cycle
+            "cycle_windows": len(windows),
+            "us_per_step_per_layer_median_cycle": float(np.median(windows)),
+            "us_per_step_per_layer_cycle_range": [float(min(windows)), float(max(windows))],
             "ms_per_step": gpu_s * 1e3 / steps,
             "wall_ms_per_step": wall_s * 1e3 / steps,
             "tokens_per_s": wl.batch * nq * steps / gpu_s,
@@ -504,7 +519,7 @@ def main():
         "value": main_res["us_per_step_per_layer"],
         "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "steps_timed": main_res["steps_timed"],      # --steps rounded up to whole eviction cycles, at least four
+        "steps_timed": main_res["steps_timed"],      # --steps rounded up to whole eviction cycles, at least sixteen
         "warmup_run": main_res["warmup_run"],        # --warmup, at least one whole eviction cycle
         "ms_per_step": main_res["ms_per_step"],
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
