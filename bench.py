@@ -51,6 +51,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=80)
+    ap.add_argument("--min-cycles", type=int, default=kMinCycles,
+                    help="single-layer workloads time at least this many whole eviction cycles (counter runs under "
+                         "rocprofv3 use 1: every kernel is serialised there)")
     ap.add_argument("--workload", default="cfg3", help="cfg1..cfg5 (default cfg3: the HBM-bound Llama-3.1-8B-shaped layer)")
     ap.add_argument("--also", default="cfg2,cfg4,cfg5", help="comma list of further workloads reported under 'others' ('' = none)")
     ap.add_argument("--split-keys", type=int, default=0)
@@ -262,7 +265,7 @@ def simulate(job, n_now, steps):
     return total_bytes, attn_bytes, evict_steps, sim
 
 
-def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=True):
+def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=True, min_cycles=kMinCycles):
     """evicts=False: a setting that is meant never to reach its trigger (the full-cache variant);
     its window is timed as given."""
     job = Job(wl, split_keys, variant, gpc, q_len)
@@ -276,7 +279,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
             # region is at least four whole cycles -- a window of a few milliseconds right after a
             # handful of warm-up calls mostly measures the host getting up to speed
             cycle = whole_cycles(wl, 1, q_len, variant)
-            steps = max(steps, kMinCycles * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 1024, q_len, variant))
+            steps = max(steps, min_cycles * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 64 * min_cycles, q_len, variant))
             warmup_run = max(warmup, cycle + 8)
     try:
         run_steps(job, warmup_run)
@@ -503,7 +506,8 @@ def main():
         torch.mul(src, 2.0, out=dst)      # shows up as one elementwise kernel of 2^28 elements
         torch.cuda.synchronize()
         del src, dst
-    main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant, args.groups_per_cu)
+    main_res = measure(wl, args.steps, args.warmup, args.split_keys, args.attn_variant, args.groups_per_cu,
+                       min_cycles=args.min_cycles)
     others = {}
     for name in [n for n in args.also.split(",") if n and n != args.workload]:
         w = wls[name]
@@ -511,7 +515,8 @@ def main():
         steps = args.steps if w.n_layers == 1 else 1
         warm = args.warmup if w.n_layers == 1 else 8
         try:
-            others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant, args.groups_per_cu)
+            others[name] = measure(w, steps, warm, args.split_keys, args.attn_variant, args.groups_per_cu,
+                                   min_cycles=args.min_cycles)
         except Exception as e:  # a side measurement must not lose the main line
             others[name] = {"error": repr(e)}
     line = {

@@ -31,10 +31,17 @@ constexpr int kD = 128;
 constexpr int kRowB = kD * 2;      // bytes per K or V row
 constexpr int kNV = kRowB / 16;    // 16-byte vectors per row
 constexpr int kTK = 32;            // keys per wave tile
-// LDS floats that stage decode logits: real rows x (keys per window).  48 KiB: a 16-row pass gets
-// 768-key windows (fewer drains: 86 -> 82 us at four query rows on the Llama-shaped layer); the
-// kernel runs one work-group per compute unit anyway (registers)
+// LDS floats that stage decode logits: real rows x (keys per window).  Every window but a piece's
+// last ends in a drain that stops the work-group's stream (stores, their acknowledgement, a barrier).
+// Single-query steps: 48 KiB (3072-key windows for the 4 rows of the Llama grouping: one window per
+// piece).  Calls with several query rows (BIGWIN): 144 KiB, which the window then shares with the
+// buffer through which the waves merge their partial results at the end of a piece -- the two are
+// never in use together -- so a 16-row pass gets 2304-key windows and a 32-row pass 1152-key ones
+// (it had 768 and 576: four query rows on the ragged Llama layer 72.3 -> 70.3 us, eight rows
+// 87.8 -> 83.0 us, sixteen 163 -> 153 us).  The kernel runs one work-group per compute unit anyway
+// (registers).
 constexpr int kLogitFloats = 12288;
+constexpr int kLogitFloatsBig = 36864;
 
 // Decode logits of the matrix-core path, written by the attention kernel and read by the finishing
 // kernel: the slot axis is cut into tiles of 64, and a tile holds all rows (head x query position)
@@ -103,7 +110,7 @@ __device__ __forceinline__ uint4 buf_load16(rsrc_t r, uint32_t lane_off, uint32_
 // it, and the slot picked by the previous step's selection is compared by value; such keys are
 // masked like keys past the end of the segment.  Work-group 0 moves that pending slot into the
 // bitmap and clears the half of `pend` that this step's finishing kernel will write.
-template <int WPB, int AUXK, int AUXV, int NB, bool LAZY>
+template <int WPB, int AUXK, int AUXV, int NB, bool LAZY, bool BIGWIN>
 __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   constexpr int kRows = 16 * NB;         // rows of a pass = rows of a partial slot
   constexpr int kThreads = WPB * 64;
@@ -116,12 +123,17 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
   const int Q = a.Q;
   const int units = s.Hkv * a.passes;
   __shared__ long long offs[kMaxBatch + 1];
-  // two row blocks: what LDS is left goes into the window (32 rows x 576 keys), since every drain
-  // stops the work-group's stream
-  constexpr int kWindow = NB > 1 ? kLogitFloats * 3 / 2 : kLogitFloats;
-  __shared__ float sm_logit[kWindow + kRows * 4];   // rows of SK + 4 floats (the pad spreads the banks)
+  constexpr int kWindow = BIGWIN ? kLogitFloatsBig : kLogitFloats;
+  // the logit window (rows of SK + 4 floats; the pad spreads the banks) and the merge buffer (every
+  // wave's accumulators, reference and sum, lane-major): side by side, or -- BIGWIN -- one buffer
+  // with two uses, the window while a piece streams, the merge buffer at its end
+  constexpr int kPartFloats = WPB * 34 * 64;
+  constexpr int kLogitBuf = kWindow + kRows * 4;
+  static_assert(!BIGWIN || kLogitBuf >= kPartFloats, "the merge buffer must fit the logit window");
+  __shared__ __align__(16) float sm_logit[kLogitBuf];
+  __shared__ float sm_merge[BIGWIN ? 1 : kPartFloats];     // (two arrays: the compiler then knows they are disjoint)
+  float (*const sm_part)[34][64] = reinterpret_cast<float (*)[34][64]>(BIGWIN ? sm_logit : sm_merge);
   __shared__ float sm_new[kRows][kTK + 4];   // logits of the appended tokens
-  __shared__ float sm_part[WPB][34][64];   // every wave's accumulators, reference and sum, lane-major
   if (wave == 0) build_offsets(s, a.lv, a.mask, units, Q + unit_extra(s), offs, lane, &a.lens);
   else if (wave == 1) warm_kernel_arguments<sizeof(MqArgs)>();   // meanwhile, for all waves of the compute unit
   __syncthreads();
@@ -494,15 +506,37 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     for (int t_lo = 0; t_lo < ntile; ++win) {
       const int t_hi = min(ntile, ntp + (win + 1) * WT);
       if (LAZY && ntd > 0) run_tiles(t_lo, t_hi, std::true_type{}, false);
-      else run_tiles(t_lo, t_hi, std::false_type{}, kEarly && t_lo == 0);
+      else run_tiles(t_lo, t_hi, std::false_type{}, kEarly && (BIGWIN || t_lo == 0));   // BIGWIN: every window finds its first tile requested
       const int wk0 = win * SK;
       const int nk = min(dp - d0 - wk0, SK);
       const bool last = t_hi == ntile;
       if (nk > 0 || (last && nta)) {
         __syncthreads();
-        for (int r = 0; r < nrows; ++r)
-          for (int key = tid; key < nk; key += kThreads)
-            a.sc.logits[logit_index(s, b, s.H * Q, row_base + r, d0 + wk0 + key)] = sm_logit[r * SKP + key];
+        if (nk > 0) {
+          // the window's slots [s_lo, s_hi) go out four at a time: an item is (row, quad of slots
+          // 4k .. 4k+3), one 16-byte store (a quad never straddles a 64-slot tile of the logit
+          // layout); the quads at the window's ends may be partial and go out float by float
+          const int s_lo = d0 + wk0, s_hi = s_lo + nk;
+          const int q_lo = s_lo & ~3;
+          const int nq = (s_hi - q_lo + 3) >> 2;
+          const bool aligned = (s_lo & 3) == 0;            // then the LDS side is 16-byte aligned as well
+          for (int item = tid; item < nrows * nq; item += kThreads) {
+            const int r = div_small(item, nq);
+            const int sq = q_lo + 4 * (item - r * nq);
+            float* dst = a.sc.logits + logit_index(s, b, s.H * Q, row_base + r, sq);
+            const float* src = sm_logit + r * SKP + (sq - s_lo);
+            if (sq >= s_lo && sq + 4 <= s_hi) {
+              float4 v;
+              if (aligned) v = *reinterpret_cast<const float4*>(src);
+              else v = make_float4(src[0], src[1], src[2], src[3]);
+              *reinterpret_cast<float4*>(dst) = v;
+            } else {
+#pragma unroll
+              for (int i = 0; i < 4; ++i)
+                if (sq + i >= s_lo && sq + i < s_hi) dst[i] = src[i];
+            }
+          }
+        }
         if (last && nta) {
           const int nn = d1 - a0;
           for (int idx = tid; idx < nrows * nn; idx += kThreads) {
@@ -511,6 +545,9 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
           }
         }
         if (!last) {
+          // the next window's first tile is requested behind the stores: the wait for the stores
+          // (loads and stores share the completion counter) then covers its round trip as well
+          if constexpr (kEarly && BIGWIN) (void)prime(t_hi, min(ntile, ntp + (win + 2) * WT), std::false_type{}, kbuf0, vbuf0);
           __builtin_amdgcn_s_waitcnt(0x0F70);
           __syncthreads();
         }
@@ -520,6 +557,11 @@ __global__ __launch_bounds__(WPB * 64) void attn_mq_kernel(const MqArgs a) {
     // waves -> one partial per piece, a block of 16 rows at a time: every wave leaves its
     // accumulators, reference and sum in LDS (lane-major, conflict-free); after one barrier, thread
     // (lane, i, q) merges four consecutive output elements over the waves and stores them.
+    // (BIGWIN: the merge buffer is the logit window; a piece with decode keys has just written its
+    // last window out, and every wave must have read its share before the buffer is overwritten.)
+    if constexpr (BIGWIN) {
+      if (ntd + nta > 0) __syncthreads();
+    }
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
       // the four lanes of a row saw different keys: add up their sums (the accumulators are
@@ -937,9 +979,9 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   }
 }
 
-template <int WPB, int AUXK = 0, int AUXV = 0, int NB = 1, bool LAZY = false>
+template <int WPB, int AUXK = 0, int AUXV = 0, int NB = 1, bool LAZY = false, bool BIGWIN = false>
 hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
-  auto kern = attn_mq_kernel<WPB, AUXK, AUXV, NB, LAZY>;
+  auto kern = attn_mq_kernel<WPB, AUXK, AUXV, NB, LAZY, BIGWIN>;
   if (occupancy) return hipOccupancyMaxActiveBlocksPerMultiprocessor(occupancy, kern, WPB * 64, 0);
   if (tm) hipExtLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, tm->start, tm->stop, 0, a);
   else hipLaunchKernelGGL(kern, dim3(n_groups), dim3(WPB * 64), 0, st, a);
@@ -948,7 +990,9 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
   // more than 16 rows (heads x query positions): two row blocks per pass
-  if (mq_row_blocks(a.s.G, a.Q) == 2) return launch_mq_w<8, 0, 2, 2>(a, n_groups, occupancy, st, tm);
+  if (mq_row_blocks(a.s.G, a.Q) == 2) return launch_mq_w<8, 0, 2, 2, false, true>(a, n_groups, occupancy, st, tm);
+  // several query rows in one row block: the large logit window (default variant only)
+  if (a.Q > 1 && a.s.variant == 0) return launch_mq_w<8, 0, 2, 1, false, true>(a, n_groups, occupancy, st, tm);
   // waves per work-group: variant 17 = 4, default 8 (four waves: the Llama-shaped layer 63.8 -> 65.0 us,
   // the Qwen-shaped one 26.5 -> 27.8 us, the 86 GB context unchanged; 12 waves at 168 registers: 2 % slower)
   if (a.s.variant == 17) return launch_mq_w<4, 0, 2>(a, n_groups, occupancy, st, tm);
