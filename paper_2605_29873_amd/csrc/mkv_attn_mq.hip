@@ -991,8 +991,12 @@ hipError_t launch_mq_w(const MqArgs& a, int n_groups, int* occupancy, hipStream_
 hipError_t launch_mq_v(const MqArgs& a, int n_groups, int* occupancy, hipStream_t st, const KernelTimer* tm) {
   // more than 16 rows (heads x query positions): two row blocks per pass
   if (mq_row_blocks(a.s.G, a.Q) == 2) return launch_mq_w<8, 0, 2, 2, false, true>(a, n_groups, occupancy, st, tm);
-  // several query rows in one row block: the large logit window (default variant only)
-  if (a.Q > 1 && a.s.variant == 0) return launch_mq_w<8, 0, 2, 1, false, true>(a, n_groups, occupancy, st, tm);
+  // several query rows in one row block, or a decode pool that the small window cannot hold in one
+  // go (every further window costs the work-group a drain in mid-stream): the large logit window
+  // (default variant only)
+  const int rows_most = (a.s.G < a.HP ? a.s.G : a.HP) * a.Q;
+  if ((a.Q > 1 || (long long)a.s.cap * rows_most > kLogitFloats) && a.s.variant == 0 && !a.s.lazy)
+    return launch_mq_w<8, 0, 2, 1, false, true>(a, n_groups, occupancy, st, tm);
   // waves per work-group: variant 17 = 4, default 8 (four waves: the Llama-shaped layer 63.8 -> 65.0 us,
   // the Qwen-shaped one 26.5 -> 27.8 us, the 86 GB context unchanged; 12 waves at 168 registers: 2 % slower)
   if (a.s.variant == 17) return launch_mq_w<4, 0, 2>(a, n_groups, occupancy, st, tm);

@@ -33,6 +33,7 @@ def _wl(G, Hkv, budget, W, alpha=0.8, M=(60, 260), batch=3, **kw):
     (12, 4, 130, 10, False, 0, 11),       # 48 heads: the general finishing kernel
     (4, 2, 64, 8, False, 64 + 1 + 3, 1000),   # three spare slots only: a compaction every third step
     (2, 1, 40, 5, False, 40 + 1 + 100, 1000), # more spare slots than live tokens
+    (7, 2, 1750, 32, False, 0, 211),      # a pool beyond the 1728 keys that this kernel's logit window holds at 7 rows
 ])
 def test_deferred_compaction_free_run_under_the_oracle(mkv, G, Hkv, budget, W, per_head, capacity, read_every):
     wl = _wl(G, Hkv, budget, W)

@@ -83,10 +83,11 @@ def test_empty_prefill_and_empty_pool(mkv):
     _chunks(ls, 48, [4], check_abar=True)
 
 
-@pytest.mark.parametrize("G,Q", [(4, 4), (7, 2)])
-def test_decode_pool_longer_than_one_logit_window(mkv, G, Q):
-    # the kernel stages decode logits in LDS windows of 384 keys
-    n_d = 1000
+@pytest.mark.parametrize("G,Q,n_d", [(4, 4, 2400), (7, 2, 2700), (4, 8, 1300), (4, 16, 1300), (4, 4, 1000)])
+def test_decode_pool_longer_than_one_logit_window(mkv, G, Q, n_d):
+    # the kernel stages decode logits in LDS windows of 36864 floats: 2304 keys at 16 rows, 2624 at
+    # 14, 1152 at 32 rows (two row blocks; sixteen query rows take two passes of 32); the last case
+    # fits one window
     wl = _small(G, 2, decode_budget=n_d, evict_trigger=n_d + 5, recent_window=5, alpha=0.9, hh_prob=0.02)
     for split in (0, 64):
         ls = Lockstep(mkv, wl, split_keys=split, max_q_len=Q)

@@ -305,10 +305,13 @@ def test_random_shapes_lockstep(mkv, i):
     assert ls.evictions >= 1 or steps > 160
 
 
-@pytest.mark.parametrize("G,n_d", [(7, 1700), (8, 800), (4, 3300), (1, 6500), (2, 3200)])
+@pytest.mark.parametrize("G,n_d", [(7, 1700), (7, 1740), (8, 800), (8, 4700), (16, 2500), (4, 3300), (4, 9500),
+                                   (1, 6500), (2, 3200)])
 def test_decode_pools_longer_than_one_logit_window(mkv, G, n_d):
-    # the attention kernel stages decode logits in LDS windows (768 .. 6144 keys depending on the
-    # head grouping): pools longer than a window, cut at odd places by 64-key and automatic ranges
+    # the attention kernel stages decode logits in LDS windows: 12288 floats (G rows x keys) when the
+    # whole pool fits, else 36864 floats.  Pools around and beyond a window, cut at odd places by
+    # 64-key and automatic ranges: (7, 1740) two small windows of 1728 keys; (8, 4700), (16, 2500),
+    # (4, 9500) two large windows of 4608, 2304 and 9216 keys; the others one window
     wl = X.Workload("window", batch=2, n_layers=1, n_q_heads=G * 2, n_kv_heads=2, head_dim=128, dtype="bf16",
                     prefill_min=100, prefill_max=300, decode_budget=n_d, evict_trigger=n_d + 1,
                     recent_window=5, alpha=0.9, steps=0, hh_prob=0.02)
