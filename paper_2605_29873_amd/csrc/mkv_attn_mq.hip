@@ -687,9 +687,15 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   extern __shared__ float smem[];  // slot blocks: [rows] normalisers + exchange space
 
   const int row_blocks = (rows + kRowsPerBlock - 1) / kRowsPerBlock;
-  if ((int)blockIdx.x < row_blocks) {
+  // Order of the blocks along x.  ONE: row blocks first (everything is resident at once).  Otherwise
+  // the slot blocks come first: a launch has more blocks than the chip holds, the slot blocks are
+  // the long ones (two dependent round trips), and blocks start in index order.
+  const int slot_blocks = (int)gridDim.x - row_blocks;
+  const int rblk = ONE ? (int)blockIdx.x : (int)blockIdx.x - slot_blocks;
+  const int sblk = ONE ? (int)blockIdx.x - row_blocks : (int)blockIdx.x;
+  if (rblk >= 0 && rblk < row_blocks) {
     // one wave per row, a lane per pair of output elements: no LDS, no barrier
-    const int x = (int)blockIdx.x * kRowsPerBlock + (tid >> 6);
+    const int x = rblk * kRowsPerBlock + (tid >> 6);
     if (x >= rows) return;
     const int qi = x / s.H, h = x - qi * s.H;
     const RowSpan sp = row_span(a, off_b, b, h, qi, Lb);
@@ -746,7 +752,7 @@ __global__ __launch_bounds__(kFinishThreads) void finish_mq_kernel(const FinishM
   // slots per slot block: a thread per slot (ONE), or a lane per slot with the query rows dealt out
   // to the four waves
   constexpr int kSlots = ONE ? kFinishThreads : kSlotsMulti;
-  const int jb = ((int)blockIdx.x - row_blocks) * kSlots;
+  const int jb = sblk * kSlots;
   if (jb >= n1) return;
   const int j = jb + (ONE ? tid : lane);
   // ONE: the slot's logits are fetched before the normalisers are rebuilt, so that the two memory
