@@ -276,7 +276,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
         steps = whole_cycles(wl, steps, q_len, variant)
         if wl.n_layers == 1:
             # steady state (cf. the docstring): the warm-up passes the first eviction, and the timed
-            # region is at least four whole cycles -- a window of a few milliseconds right after a
+            # region is at least min_cycles whole cycles -- a window of a few milliseconds right after a
             # handful of warm-up calls mostly measures the host getting up to speed
             cycle = whole_cycles(wl, 1, q_len, variant)
             steps = max(steps, min_cycles * cycle) if cycle >= 16 else max(steps, whole_cycles(wl, 64 * min_cycles, q_len, variant))
