@@ -324,6 +324,7 @@ def measure(wl, steps, warmup, split_keys=0, variant=0, gpc=0, q_len=0, evicts=T
             "finish_kernel_us": prof["finish_us"] / n_launch,
             "evict_us_per_evicting_launch": (prof["evict_us"] / pevict) if pevict else None,
             "evicting_launches": int(pevict),
+            "evict_us_per_step_amortised": prof["evict_us"] / n_launch,   # the eviction kernels' share of a step
             "attn_algorithmic_bytes_per_launch": attn_bytes / steps,
             "attn_GBps": (attn_bytes / steps) / (prof["attn_us"] / n_launch * 1e-6) / 1e9,
             "arena_GB": job.arena_bytes / 1e9,
@@ -541,6 +542,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": attn_kernel_name(wl, args.attn_variant),
                      "achieved": main_res["attn_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": main_res["attn_GBps"] / HBM_PEAK_GBPS, "traffic": measured_traffic(args.workload),
+                     # the counters' bytes over the same launch time, beside the algorithmic figure
+                     "traffic_GBps": (measured_traffic(args.workload) / (main_res["attn_kernel_us"] * 1e-6) / 1e9
+                                      if measured_traffic(args.workload) else None),
                      "traffic_source": f"profiles/{args.workload}_pmc.txt (rocprofv3 FETCH_SIZE/WRITE_SIZE, bytes per launch)",
                      "algorithmic_bytes_per_launch": main_res["attn_algorithmic_bytes_per_launch"],
                      "avg_launch_us": main_res["attn_kernel_us"],
