@@ -41,7 +41,27 @@ def build_library(verbose: bool = False, extra_flags: list[str] | None = None) -
             print(text)
     cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB_PATH]
     subprocess.run(cmd, check=True)
+    build_c_driver(verbose)
     return LIB_PATH
+
+
+# A caller of the C ABI written in plain C99 (tests/abi_gpu_driver.c): device memory from hipMalloc,
+# no Python in the process.  Built here, next to the library, so that it travels with it; a GPU
+# test runs it.
+C_DRIVER_PATH = os.path.join(HERE, "abi_gpu_driver.bin")
+
+
+def build_c_driver(verbose: bool = False) -> str:
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.path.join(rocm, "llvm", "bin", "clang"), "-std=c99", "-O1", "-Wall", "-Werror",
+           "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(ROOT, "include"), "-I", os.path.join(rocm, "include"),
+           os.path.join(ROOT, "tests", "abi_gpu_driver.c"), "-o", C_DRIVER_PATH,
+           "-L", HERE, "-lmkv", "-L", os.path.join(rocm, "lib"), "-lamdhip64",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_DRIVER_PATH
 
 
 if __name__ == "__main__":
