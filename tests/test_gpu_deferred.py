@@ -222,16 +222,19 @@ def test_rows_from_the_producer_on_a_context_with_deferred_compaction(mkv):
 def test_cfg4_qwen_layer_deferred_compaction_from_an_empty_pool(mkv, capsys):
     """The Qwen-shaped layer at full size in the configuration the bench times (default capacity:
     64 spare slots), all 8 sequences active, 1500 steps from an empty pool; sequences 2 and 7 are
-    followed, the readers look every 200 steps."""
+    followed, the readers look every 200 steps.  MKV_TEST_CFG4_STEPS=16384 in the environment makes
+    it the workload's whole run (about seven minutes, the oracle's)."""
+    import os
     wl = WL["cfg4"]
+    steps = int(os.environ.get("MKV_TEST_CFG4_STEPS", "1500"))
     dr = DeferredRun(mkv, wl, seqs=[2, 7], active=range(wl.batch))
     alive = Progress(capsys, "cfg4 deferred")
     try:
         dr.prefill()
-        for t in range(1500):
-            dr.step(t, read=(t % 200 == 199 or t == 1499), check_abar=(t % 50 == 0))
-            alive.tick(f"step {t} of 1500, {dr.evictions} evictions")
-        assert dr.evictions == 2 * (1500 - 512) and dr.max_holes >= 60
+        for t in range(steps):
+            dr.step(t, read=(t % 200 == 199 or t == steps - 1), check_abar=(t % 50 == 0))
+            alive.tick(f"step {t} of {steps}, {dr.evictions} evictions")
+        assert dr.evictions == 2 * (steps - 512) and dr.max_holes >= 60
     finally:
         dr.close()
     spread = np.percentile(dr.evicted_slots, [0, 25, 50, 75, 100]).astype(int).tolist()
